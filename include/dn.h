@@ -1,0 +1,152 @@
+/*
+ * dn.h -- C-ABI of libdn: the subsampled Gauss-Newton path of the Newton method for
+ * fully-connected networks ("Distributed Newton Methods for Deep Neural Networks"), on one
+ * AMD MI355X (gfx950).
+ *
+ * Network n_0-n_1-...-n_L, sigmoid hidden layers, linear output layer, squared loss
+ * (Section 2.1, Section 3.3.2).  Notation follows the paper: W^m is n_{m-1} x n_m,
+ * s^{m,i} = (W^m)^T z^{m-1,i} + b^m, z^{m,i} = sigma(s^{m,i}), l samples, n parameters.
+ *
+ * Conventions for every call
+ *   - All array arguments are DEVICE pointers to fp32 unless the name ends in _host.
+ *     Matrices are dense row-major with the sample index leading: X is [l x n_0],
+ *     Y is [l x n_L] (one-hot class targets, or any real targets).
+ *   - Parameter-shaped vectors (theta, g, v, out, d) use the layout of Section 2.1:
+ *     for m = 1..L the n_m x n_{m-1} matrix (W^m)^T row-major, then the n_m biases.
+ *   - The caller owns every buffer.  The library borrows argument pointers for the duration
+ *     of the call only, except the workspace given to dn_bind, which it keeps using until the
+ *     context is destroyed or re-bound.  The library itself allocates no device memory.
+ *   - Work is enqueued on the HIP stream given to dn_bind.  Calls that return a host scalar
+ *     (f, iteration counts, residual norms) synchronise that stream before returning; the
+ *     others return as soon as the work is enqueued.
+ *   - Every call returns DN_OK (0) or a negative error code; nothing is thrown across the ABI.
+ *     Arguments are validated on the host before anything is launched.
+ */
+#ifndef DN_H
+#define DN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dn_ctx dn_ctx;
+
+enum {
+    DN_OK = 0,
+    DN_EINVAL = -1,   /* null pointer, non-positive size, s > s_max, l > l_max, bad mode or layer */
+    DN_ENOSPC = -2,   /* workspace given to dn_bind is smaller than dn_workspace_bytes() */
+    DN_ESTATE = -3,   /* call needs a bound workspace / a prior dn_jacobian_prep and there is none */
+    DN_EHIP = -4,     /* a HIP runtime call failed; dn_last_hip_error() gives the HIP code */
+    DN_ENOMEM = -5    /* host allocation failed */
+};
+
+/* mode of dn_gn_matvec and dn_cg */
+enum {
+    DN_FULL = 0,      /* whole subsampled Gauss-Newton matrix (Section 4.3) */
+    DN_BLOCKDIAG = 1  /* its diagonal blocks, one block per layer = W^m with b^m (Section 4.1) */
+};
+
+/* Human-readable text for an error code (static storage). */
+const char* dn_strerror(int code);
+
+/*
+ * Create a context for the network dims[0..L] (L >= 1 weight layers, every entry >= 1) with
+ * regularisation parameter C > 0 of the objective (Section 2.1).  l_max / s_max bound the
+ * number of rows later passed to dn_forward / dn_grad and the subsample size passed to
+ * dn_jacobian_prep; they size the workspace.  Host-only: touches no device.
+ */
+int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_max);
+void dn_destroy(dn_ctx* ctx);
+
+/* n = sum_m (n_{m-1} n_m + n_m)  (Section 2.1).  0 if ctx is null. */
+size_t dn_num_params(const dn_ctx* ctx);
+
+/* Bytes of device workspace the context needs (activations for l_max rows, the stored
+ * Jacobian blocks and activations for s_max rows, product temporaries, CG vectors). */
+size_t dn_workspace_bytes(const dn_ctx* ctx);
+
+/*
+ * Lend the context a device workspace of at least dn_workspace_bytes() bytes, 256-byte
+ * aligned, and the HIP stream (hipStream_t passed as void*, NULL = default stream) on which
+ * all later work is enqueued.  Invalidates a previous dn_jacobian_prep.
+ */
+int dn_bind(dn_ctx* ctx, void* d_workspace, size_t bytes, void* hip_stream);
+
+/*
+ * Objective value (Section 2.1):
+ *   f = theta^T theta / (2C) + (1/l) sum_i || z^{L,i} - y^i ||^2 .
+ * l <= l_max rows of X and Y are used.  *f_host receives f (fp64 accumulation of fp32 terms).
+ * If ZL is non-null it receives the network outputs, [l x n_L] dense.
+ */
+int dn_forward(dn_ctx* ctx, const float* theta, const float* X, const float* Y, int l,
+               double* f_host, float* ZL);
+
+/*
+ * Gradient by back-propagation (Section 2.2, Section 3.4):
+ *   g = theta/C + (1/l) sum_i (J^i)^T 2 (z^{L,i} - y^i),   g in theta layout.
+ * f_host may be null; otherwise it receives f as dn_forward does (and the call synchronises).
+ */
+int dn_grad(dn_ctx* ctx, const float* theta, const float* X, const float* Y, int l,
+            float* g, double* f_host);
+
+/*
+ * Prepare the subsampled Gauss-Newton matrix for the rows S of X (Section 3.3, Section 4.3):
+ * forward pass on the s = |S| selected rows keeping z^{m,i}, then the n_L simultaneous
+ * backward sweeps that produce and store
+ *   P^m_i[u][j] = d z^{L,i}_u / d s^{m,i}_j ,  m = 1..L-1      (P^L_i is the identity)
+ * in the workspace.  S is a DEVICE array of s row indices into X, each in [0, l); repeated
+ * indices are allowed (they simply count twice).  1 <= s <= s_max.
+ * theta and X need not stay alive afterwards: everything the products need is in the workspace.
+ */
+int dn_jacobian_prep(dn_ctx* ctx, const float* theta, const float* X, int l, const int* S, int s);
+
+/*
+ * Copy stored block P^m (1 <= m <= L-1) to P_out as a dense [s][n_L][n_m] array.  For tests and
+ * inspection; needs a prior dn_jacobian_prep.
+ */
+int dn_jacobian_read(dn_ctx* ctx, int m, float* P_out);
+
+/*
+ * out = G^S v  (no damping term), computed from the stored blocks by the factored products of
+ * Section 4.2:
+ *   DN_FULL:       out = v/C + (1/|S|) sum_{i in S} (J^i)^T B^i J^i v,            B^i = 2I
+ *   DN_BLOCKDIAG:  out_m = v_m/C + (1/|S|) sum_{i in S} (J^i_m)^T B^i J^i_m v_m   for each layer m
+ * v and out must not overlap.  Needs a prior dn_jacobian_prep.
+ */
+int dn_gn_matvec(dn_ctx* ctx, const float* v, float* out, int mode);
+
+/*
+ * Conjugate gradient on (G^S + lambda I) d = -g  (Section 2.2, Section 4.3), d_0 = 0, no
+ * preconditioner, at most max_iter >= 1 iterations.  After every iteration the recurrence residual
+ * r is tested: stop when ||r|| <= sigma ||g||  (Section 4.1).  sigma = 0 runs exactly max_iter
+ * iterations without any host synchronisation inside the loop.
+ * DN_BLOCKDIAG solves the L per-layer systems independently (own step lengths, own test;
+ * a block that met its test is frozen).
+ * Outputs: d (device, theta layout); *iters_host = iterations run; resnorm_host[0] (DN_FULL) or
+ * resnorm_host[0..L-1] (DN_BLOCKDIAG) = final ||r|| per system.  Dot products are accumulated
+ * in fp64.  g and d must not overlap.  Needs a prior dn_jacobian_prep.
+ */
+int dn_cg(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter, int mode,
+          float* d, int* iters_host, double* resnorm_host);
+
+/*
+ * Kernel timing.  With profiling enabled every launch of the library's kernels is bracketed
+ * by HIP events on the bound stream; dn_profile_read returns, for kernel class `which`
+ * (0 <= which < dn_profile_num_classes()), the summed duration in milliseconds and the
+ * number of launches since the last dn_profile_reset.  Reading synchronises the stream.
+ */
+int dn_profile_enable(dn_ctx* ctx, int on);
+int dn_profile_reset(dn_ctx* ctx);
+int dn_profile_num_classes(void);
+const char* dn_profile_class_name(int which);
+int dn_profile_read(dn_ctx* ctx, int which, double* total_ms_host, long long* launches_host);
+
+/* HIP error code of the most recent DN_EHIP on this context (0 if none). */
+int dn_last_hip_error(const dn_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DN_H */

@@ -1,0 +1,273 @@
+"""fp64 CPU oracle for the subsampled Gauss-Newton path.  TEST INFRASTRUCTURE ONLY.
+
+Plain numpy, float64, written from the paper's definitions.  It shares no code
+with the HIP library and must never be imported by the product package; only
+tests, the smoke check and the CPU-baseline leg of the benchmark call it.
+
+What is computed, and from where in the paper:
+
+* forward pass, objective f                     Section 2.1 (forward recursion, objective,
+                                                squared loss); sigmoid hidden / linear
+                                                output: Section 3.3.2
+* gradient by back-propagation                  Section 2.2 (the four back-propagation
+                                                equations), Section 3.4 (seed 2(z^L - y))
+* J_i v  (forward-mode directional derivative of z^{L,i}) and
+  sum_i J_i^T w_i (reverse sweep)               definition of J^i in Section 2.1
+* G^S v = v/C + (1/|S|) sum_{i in S} J_i^T B_i J_i v, B_i = 2 I
+                                                Section 4.3 (subsampled Gauss-Newton
+                                                matrix), Section 3.1 (B for squared loss)
+* block-diagonal product, one block per layer   Section 4.1
+* conjugate gradient on (G^S + lambda I) d = -g Section 2.2 / 4.3 linear system, Section 4.1
+                                                stopping rule
+* the stored blocks P^m_i = d z^{L,i} / d s^{m,i} by the backward recursion
+                                                Section 3.3 (recursion for dz^L/dz^{m-1},
+                                                product form of the Jacobian element)
+
+The G v products here never build P: they differentiate the network directly,
+so they are independent of the factored method the HIP path implements.
+
+Pins (tests/test_oracle_pins.py): finite differences of f and of the network
+outputs, brute-force dense G from an explicitly assembled Jacobian, symmetry,
+positive definiteness, the gradient-through-Jacobian identity of Section 3.4,
+the no-hidden-layer case against a normal-equations ridge solve, CG against a
+dense solve and its first-step closed form.  No function here is unpinned.
+
+theta layout (Section 2.1): for m = 1..L, the n_m x n_{m-1} matrix A^m = (W^m)^T
+stored row-major, then b^m.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- layout
+
+def num_params(dims):
+    """n = sum_m (n_{m-1} n_m + n_m), Section 2.1."""
+    return sum(dims[m - 1] * dims[m] + dims[m] for m in range(1, len(dims)))
+
+
+def unpack(theta, dims):
+    """Views (A^m, b^m), m = 1..L, of a theta-layout vector.  A^m = (W^m)^T is n_m x n_{m-1}."""
+    theta = np.asarray(theta, dtype=np.float64)
+    assert theta.shape == (num_params(dims),)
+    out = []
+    o = 0
+    for m in range(1, len(dims)):
+        nw = dims[m - 1] * dims[m]
+        A = theta[o:o + nw].reshape(dims[m], dims[m - 1])
+        o += nw
+        b = theta[o:o + dims[m]]
+        o += dims[m]
+        out.append((A, b))
+    return out
+
+
+def block_slices(dims):
+    """Slice of theta owned by layer m (weights and biases), m = 1..L."""
+    out = []
+    o = 0
+    for m in range(1, len(dims)):
+        sz = dims[m - 1] * dims[m] + dims[m]
+        out.append(slice(o, o + sz))
+        o += sz
+    return out
+
+
+# --------------------------------------------------------------------------- forward, f
+
+def forward(theta, dims, X):
+    """Z^0..Z^L, one row per sample.
+
+    s^m = (W^m)^T z^{m-1} + b^m; z^m = 1/(1+exp(-s^m)) for m < L, z^L = s^L
+    (Section 2.1 forward recursion, Section 3.3.2 activation).
+    """
+    L = len(dims) - 1
+    Z = [np.asarray(X, dtype=np.float64)]
+    for m, (A, b) in enumerate(unpack(theta, dims), start=1):
+        S = Z[-1] @ A.T + b
+        Z.append(S if m == L else 1.0 / (1.0 + np.exp(-S)))
+    return Z
+
+
+def loss(theta, dims, C, X, Y):
+    """f = theta^T theta / (2C) + (1/l) sum_i ||z^{L,i} - y^i||^2  (Section 2.1; no 1/2 on the loss)."""
+    theta = np.asarray(theta, dtype=np.float64)
+    ZL = forward(theta, dims, X)[-1]
+    D = ZL - np.asarray(Y, dtype=np.float64)
+    return float(theta @ theta / (2.0 * C) + np.sum(D * D) / X.shape[0])
+
+
+# --------------------------------------------------------------------------- gradient
+
+def _reverse_sweep(theta, dims, Z, seed):
+    """sum_i J_i^T seed_i in theta layout, by one backward sweep.
+
+    delta^L = seed (sigma' = 1 at the output layer); for each layer the weight part is
+    sum_i delta^{m,i} z^{m-1,i T}, the bias part sum_i delta^{m,i}; then
+    delta^{m-1} = (W^m delta^m) * z^{m-1}(1 - z^{m-1})   (Section 2.2 back-propagation).
+    """
+    L = len(dims) - 1
+    layers = unpack(theta, dims)
+    out = np.zeros(num_params(dims))
+    parts = unpack_mutable(out, dims)
+    delta = np.asarray(seed, dtype=np.float64)
+    for m in range(L, 0, -1):
+        A, _ = layers[m - 1]
+        gA, gb = parts[m - 1]
+        gA[...] = delta.T @ Z[m - 1]
+        gb[...] = delta.sum(axis=0)
+        if m > 1:
+            zp = Z[m - 1]
+            delta = (delta @ A) * (zp * (1.0 - zp))
+    return out
+
+
+def unpack_mutable(vec, dims):
+    """Writable (A^m, b^m) views of a float64 theta-layout vector."""
+    assert vec.dtype == np.float64 and vec.shape == (num_params(dims),)
+    out = []
+    o = 0
+    for m in range(1, len(dims)):
+        nw = dims[m - 1] * dims[m]
+        A = vec[o:o + nw].reshape(dims[m], dims[m - 1])
+        o += nw
+        b = vec[o:o + dims[m]]
+        o += dims[m]
+        out.append((A, b))
+    return out
+
+
+def grad(theta, dims, C, X, Y):
+    """(grad f, f).  grad f = theta/C + (1/l) sum_i J_i^T 2(z^{L,i} - y^i)  (Sections 2.1, 2.2, 3.4)."""
+    theta = np.asarray(theta, dtype=np.float64)
+    l = X.shape[0]
+    Z = forward(theta, dims, X)
+    D = Z[-1] - np.asarray(Y, dtype=np.float64)
+    g = theta / C + _reverse_sweep(theta, dims, Z, 2.0 * D) / l
+    f = float(theta @ theta / (2.0 * C) + np.sum(D * D) / l)
+    return g, f
+
+
+# --------------------------------------------------------------------------- J v, J^T w
+
+def jv(theta, dims, Z, v):
+    """Rows J_i v: derivative of z^{L,i} along direction v in parameter space.
+
+    Differentiating the forward recursion: sdot^m = Vw^m z^{m-1} + vb^m + A^m zdot^{m-1},
+    zdot^0 = 0, zdot^m = sigma'(s^m) * sdot^m (m < L), J_i v = sdot^L.
+    """
+    L = len(dims) - 1
+    layers = unpack(theta, dims)
+    vparts = unpack(v, dims)
+    zdot = np.zeros_like(Z[0])
+    for m in range(1, L + 1):
+        A, _ = layers[m - 1]
+        VA, vb = vparts[m - 1]
+        sdot = Z[m - 1] @ VA.T + vb + zdot @ A.T
+        zdot = sdot if m == L else sdot * (Z[m] * (1.0 - Z[m]))
+    return zdot
+
+
+def gn_matvec(theta, dims, C, XS, v):
+    """G^S v = v/C + (1/|S|) sum_{i in S} J_i^T (2 J_i v)   (Section 4.3, B = 2I from Section 3.1).
+
+    XS holds the rows of the subsample S.  No damping term is included.
+    """
+    theta = np.asarray(theta, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    Z = forward(theta, dims, XS)
+    R = jv(theta, dims, Z, v)
+    return v / C + _reverse_sweep(theta, dims, Z, 2.0 * R) / XS.shape[0]
+
+
+def gn_matvec_blockdiag(theta, dims, C, XS, v):
+    """Block-diagonal product, one block per layer (W^m together with b^m), Section 4.1.
+
+    Taken literally: for each block m, zero the other blocks of v, apply the full
+    product, keep block m of the result.
+    """
+    v = np.asarray(v, dtype=np.float64)
+    out = np.zeros_like(v)
+    for sl in block_slices(dims):
+        vm = np.zeros_like(v)
+        vm[sl] = v[sl]
+        out[sl] = gn_matvec(theta, dims, C, XS, vm)[sl]
+    return out
+
+
+# --------------------------------------------------------------------------- CG
+
+def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history=False):
+    """Conjugate gradient on (G^S + lam I) d = -g  (Sections 2.2, 4.3).
+
+    d_0 = 0, r_0 = -g, p_0 = r_0, no preconditioner.  After each step the recurrence
+    residual is tested against sigma ||g|| (Section 4.1 stopping rule).  With
+    blockdiag=True the L per-layer systems are solved independently, each block with
+    its own step lengths and its own stopping test; a block that has met its test is
+    left unchanged afterwards.
+
+    Returns (d, iterations, residual norms); residual norms has one entry (full) or one
+    per layer (block-diagonal).  With history=True also the list of iterates d_1, d_2, ...
+    """
+    g = np.asarray(g, dtype=np.float64)
+    n = g.shape[0]
+    blocks = block_slices(dims) if blockdiag else [slice(0, n)]
+    product = gn_matvec_blockdiag if blockdiag else gn_matvec
+    d = np.zeros(n)
+    r = -g.copy()
+    p = r.copy()
+    rho = np.array([r[b] @ r[b] for b in blocks])
+    gnorm = np.sqrt(np.array([g[b] @ g[b] for b in blocks]))
+    active = np.ones(len(blocks), dtype=bool)
+    # a block with zero right-hand side is already solved
+    active &= rho > 0.0
+    iters = 0
+    hist = []
+    while iters < max_iter and active.any():
+        q = product(theta, dims, C, XS, p) + lam * p
+        for k, b in enumerate(blocks):
+            if not active[k]:
+                continue
+            alpha = rho[k] / (p[b] @ q[b])
+            d[b] += alpha * p[b]
+            r[b] -= alpha * q[b]
+            rho_new = r[b] @ r[b]
+            if np.sqrt(rho_new) <= sigma * gnorm[k]:
+                active[k] = False
+            else:
+                p[b] = r[b] + (rho_new / rho[k]) * p[b]
+            rho[k] = rho_new
+        iters += 1
+        if history:
+            hist.append(d.copy())
+    res = np.sqrt(rho)
+    if history:
+        return d, iters, res, hist
+    return d, iters, res
+
+
+# --------------------------------------------------------------------------- stored Jacobian blocks
+
+def jacobian_blocks(theta, dims, XS):
+    """P^m, m = 1..L, with P^m[i, u, j] = d z^{L,i}_u / d s^{m,i}_j   (Section 3.3).
+
+    dz^L/dz^L is the identity; dz^L/ds^m = dz^L/dz^m * sigma'(s^m);
+    dz^L/dz^{m-1}_t = sum_j dz^L/ds^m_j * w^m_{tj}.
+    """
+    L = len(dims) - 1
+    layers = unpack(theta, dims)
+    Z = forward(theta, dims, XS)
+    s = XS.shape[0]
+    nL = dims[L]
+    P = [None] * (L + 1)
+    dz = np.broadcast_to(np.eye(nL), (s, nL, nL)).copy()      # dz^L/dz^L
+    for m in range(L, 0, -1):
+        if m == L:
+            P[m] = dz                                           # sigma' = 1 at the output layer
+        else:
+            P[m] = dz * (Z[m] * (1.0 - Z[m]))[:, None, :]
+        if m > 1:
+            A, _ = layers[m - 1]                                # A[j, t] = w^m_{tj}
+            dz = P[m] @ A                                       # [s, nL, n_{m-1}]
+    return P[1:]

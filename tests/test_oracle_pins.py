@@ -1,0 +1,350 @@
+"""Pins of the fp64 oracle against things other than itself (CPU only).
+
+Each test names what it would catch.  References used: scalar-loop forward pass and
+finite differences (tests/tiny_ref.py), torch float64 autograd on an independently
+written model, hand-derived closed forms, numpy dense solves.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import dn_inputs
+from oracle import dn_oracle as orc
+from tests import tiny_ref
+
+TINY_NETS = [
+    (3, 2, 2),          # one hidden layer
+    (4, 3, 3, 2),       # two hidden layers
+    (2, 3, 2, 3, 2),    # three hidden layers
+    (5, 3),             # no hidden layer
+]
+
+
+def _tiny(dims, l=6, s=4, C=0.7, seed=7):
+    cfg = dn_inputs.custom(dims, l=l, s=s, C=C, seed=seed)
+    X = dn_inputs.make_X(cfg).astype(np.float64)
+    Y = dn_inputs.make_Y(cfg).astype(np.float64)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.5).astype(np.float64)
+    S = dn_inputs.make_subset(cfg)
+    return cfg, X, Y, theta, S
+
+
+def _torch_model(theta, dims):
+    """Independent torch float64 model reading the theta layout of Section 2.1."""
+    offs = dn_inputs.layer_offsets(dims)
+    L = len(dims) - 1
+
+    def f(th, X):
+        z = X
+        for m in range(1, L + 1):
+            w, b = offs[m - 1]
+            A = th[w:w + dims[m - 1] * dims[m]].reshape(dims[m], dims[m - 1])
+            z = torch.nn.functional.linear(z, A, th[b:b + dims[m]])
+            if m < L:
+                z = torch.sigmoid(z)
+        return z
+    return f
+
+
+# ------------------------------------------------------------------ forward / f
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_forward_and_f_match_scalar_loops(dims):
+    # catches: transposed weight layout, bias offset errors, sigmoid on the output layer, 1/2 on the loss
+    cfg, X, Y, theta, _ = _tiny(dims)
+    Z = orc.forward(theta, dims, X)
+    for i in range(X.shape[0]):
+        np.testing.assert_allclose(Z[-1][i], tiny_ref.net_output(theta, dims, X[i]), rtol=1e-13, atol=1e-14)
+    f = orc.loss(theta, dims, cfg.C, X, Y)
+    assert abs(f - tiny_ref.objective(theta, dims, cfg.C, X, Y)) <= 1e-13 * abs(f)
+
+
+def test_f_closed_form_one_weight():
+    # 1-1 network, one sample: f = (w^2 + b^2)/(2C) + (w x + b - y)^2
+    dims = (1, 1)
+    w, b, x, y, C = 0.3, -0.2, 0.9, 1.0, 2.0
+    f = orc.loss(np.array([w, b]), dims, C, np.array([[x]]), np.array([[y]]))
+    assert abs(f - ((w * w + b * b) / (2 * C) + (w * x + b - y) ** 2)) < 1e-15
+
+
+# ------------------------------------------------------------------ gradient
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_gradient_vs_finite_differences(dims):
+    # catches: missing factor 2 in the seed, 1/l scaling, theta/C term, wrong sigma'
+    cfg, X, Y, theta, _ = _tiny(dims)
+    g, f = orc.grad(theta, dims, cfg.C, X, Y)
+    g_fd = tiny_ref.fd_gradient(theta, dims, cfg.C, X, Y)
+    assert np.linalg.norm(g - g_fd) <= 1e-7 * np.linalg.norm(g_fd)
+    assert abs(f - tiny_ref.objective(theta, dims, cfg.C, X, Y)) <= 1e-13 * abs(f)
+
+
+def test_gradient_vs_torch_autograd_config1():
+    cfg = dn_inputs.config(1)
+    X = dn_inputs.make_X(cfg).astype(np.float64)
+    Y = dn_inputs.make_Y(cfg).astype(np.float64)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.3).astype(np.float64)
+    g, f = orc.grad(theta, cfg.dims, cfg.C, X, Y)
+    th = torch.tensor(theta, requires_grad=True)
+    model = _torch_model(theta, cfg.dims)
+    ft = th @ th / (2 * cfg.C) + ((model(th, torch.tensor(X)) - torch.tensor(Y)) ** 2).sum() / cfg.l
+    ft.backward()
+    assert abs(f - ft.item()) <= 1e-13 * abs(f)
+    np.testing.assert_allclose(g, th.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+# ------------------------------------------------------------------ Jacobian, J v, J^T w
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_jv_and_jt_vs_explicit_jacobian(dims):
+    # catches: wrong Jacobian seed (identity, not the loss derivative), transposed operands in J^T
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    rng = np.random.default_rng(3)
+    v = rng.standard_normal(theta.size)
+    W = rng.standard_normal((XS.shape[0], dims[-1]))
+    Z = orc.forward(theta, dims, XS)
+    R = orc.jv(theta, dims, Z, v)
+    acc = np.zeros(theta.size)
+    for i in range(XS.shape[0]):
+        J = tiny_ref.fd_jacobian(theta, dims, XS[i])
+        np.testing.assert_allclose(R[i], J @ v, rtol=1e-7, atol=1e-9)
+        acc += J.T @ W[i]
+    got = orc._reverse_sweep(theta, dims, Z, W)
+    assert np.linalg.norm(got - acc) <= 1e-7 * np.linalg.norm(acc)
+
+
+def test_jacobian_vs_torch_autograd():
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims)
+    model = _torch_model(theta, dims)
+    Z = orc.forward(theta, dims, X[S])
+    for i in range(len(S)):
+        xi = torch.tensor(X[S[i]])
+        J = torch.autograd.functional.jacobian(lambda th: model(th, xi[None])[0], torch.tensor(theta)).numpy()
+        for k in range(3):
+            e = np.zeros(theta.size); e[5 * k + 1] = 1.0
+            np.testing.assert_allclose(orc.jv(theta, dims, [z[i:i + 1] for z in Z], e)[0], J[:, 5 * k + 1],
+                                       rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_stored_blocks_are_output_derivatives_wrt_s(dims):
+    # d z^L_u / d b^m_j = d z^L_u / d s^m_j (Section 3.3), so the bias columns of the
+    # finite-difference Jacobian are the stored blocks; d z^L/d w^m_{tj} = P^m[u,j] z^{m-1}_t.
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    P = orc.jacobian_blocks(theta, dims, XS)
+    Z = orc.forward(theta, dims, XS)
+    offs = dn_inputs.layer_offsets(dims)
+    L = len(dims) - 1
+    for i in range(XS.shape[0]):
+        J = tiny_ref.fd_jacobian(theta, dims, XS[i])
+        for m in range(1, L + 1):
+            w, b = offs[m - 1]
+            np.testing.assert_allclose(P[m - 1][i], J[:, b:b + dims[m]], rtol=1e-7, atol=1e-9)
+            Jw = J[:, w:w + dims[m - 1] * dims[m]].reshape(dims[-1], dims[m], dims[m - 1])
+            np.testing.assert_allclose(Jw, P[m - 1][i][:, :, None] * Z[m - 1][i][None, None, :], rtol=1e-6, atol=1e-9)
+    # closed forms: P^L = I, P^{L-1} = A^L diag(sigma'(s^{L-1}))
+    np.testing.assert_array_equal(P[L - 1][0], np.eye(dims[-1]))
+    if L >= 2:
+        AL = orc.unpack(theta, dims)[L - 1][0]
+        zi = Z[L - 1][1]
+        np.testing.assert_allclose(P[L - 2][1], AL * (zi * (1 - zi))[None, :], rtol=1e-13)
+
+
+def test_gradient_through_jacobian_identity():
+    # Section 3.4: grad f = theta/C + (1/l) sum_i J_i^T 2 (z^{L,i} - y^i); on the subsample this
+    # must equal back-propagation restricted to S.
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS, YS = X[S], Y[S]
+    g, _ = orc.grad(theta, dims, cfg.C, XS, YS)
+    acc = theta / cfg.C
+    for i in range(len(S)):
+        J = tiny_ref.fd_jacobian(theta, dims, XS[i])
+        z = np.array(tiny_ref.net_output(theta, dims, XS[i]))
+        acc = acc + J.T @ (2.0 * (z - YS[i])) / len(S)
+    assert np.linalg.norm(g - acc) <= 1e-7 * np.linalg.norm(acc)
+
+
+# ------------------------------------------------------------------ Gauss-Newton products
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_gn_matvec_vs_dense_brute_force(dims):
+    # catches: B = I instead of 2I, 1/l instead of 1/|S|, missing v/C
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    G = tiny_ref.dense_gauss_newton(theta, dims, cfg.C, XS)
+    rng = np.random.default_rng(5)
+    for _ in range(3):
+        v = rng.standard_normal(theta.size)
+        got = orc.gn_matvec(theta, dims, cfg.C, XS, v)
+        assert np.linalg.norm(got - G @ v) <= 1e-7 * np.linalg.norm(G @ v)
+
+
+@pytest.mark.parametrize("dims", TINY_NETS)
+def test_blockdiag_matvec_vs_dense_block_diagonal(dims):
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    G = tiny_ref.dense_gauss_newton(theta, dims, cfg.C, XS)
+    Ghat = tiny_ref.zero_offdiag_layer_blocks(G, dims)
+    v = np.random.default_rng(6).standard_normal(theta.size)
+    got = orc.gn_matvec_blockdiag(theta, dims, cfg.C, XS, v)
+    assert np.linalg.norm(got - Ghat @ v) <= 1e-7 * np.linalg.norm(Ghat @ v)
+    if len(dims) > 2:
+        assert np.linalg.norm(Ghat @ v - G @ v) > 1e-3 * np.linalg.norm(G @ v)  # the two operators differ
+
+
+def test_blockdiag_equals_full_on_single_block_support_and_for_L1():
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    rng = np.random.default_rng(8)
+    for sl in orc.block_slices(dims):
+        v = np.zeros(theta.size)
+        v[sl] = rng.standard_normal(sl.stop - sl.start)
+        full = orc.gn_matvec(theta, dims, cfg.C, XS, v)
+        hat = orc.gn_matvec_blockdiag(theta, dims, cfg.C, XS, v)
+        np.testing.assert_allclose(hat[sl], full[sl], rtol=1e-12, atol=1e-14)
+    dims1 = (5, 3)
+    cfg, X, Y, theta, S = _tiny(dims1)
+    v = rng.standard_normal(theta.size)
+    np.testing.assert_allclose(orc.gn_matvec_blockdiag(theta, dims1, cfg.C, X[S], v),
+                               orc.gn_matvec(theta, dims1, cfg.C, X[S], v), rtol=1e-13)
+
+
+def test_gn_symmetry_and_definiteness_config1():
+    cfg = dn_inputs.config(1)
+    X = dn_inputs.make_X(cfg).astype(np.float64)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.3).astype(np.float64)
+    XS = X[dn_inputs.make_subset(cfg)]
+    v = dn_inputs.make_probe(cfg, 0).astype(np.float64)
+    w = dn_inputs.make_probe(cfg, 1).astype(np.float64)
+    for product in (orc.gn_matvec, orc.gn_matvec_blockdiag):
+        Gv = product(theta, cfg.dims, cfg.C, XS, v)
+        Gw = product(theta, cfg.dims, cfg.C, XS, w)
+        assert abs(w @ Gv - v @ Gw) <= 1e-12 * abs(w @ Gv)
+        assert v @ Gv >= v @ v / cfg.C
+    # v^T G v = v^T v / C + (2/|S|) sum_i ||J_i v||^2
+    Z = orc.forward(theta, cfg.dims, XS)
+    R = orc.jv(theta, cfg.dims, Z, v)
+    Gv = orc.gn_matvec(theta, cfg.dims, cfg.C, XS, v)
+    assert abs(v @ Gv - (v @ v / cfg.C + 2.0 * np.sum(R * R) / XS.shape[0])) <= 1e-12 * abs(v @ Gv)
+
+
+def test_gn_closed_form_scalar_network():
+    # 1-1-1 network, one sample: J = [w2 s' x, w2 s', z1, 1] with z1 = sigmoid(w1 x + b1), s' = z1(1-z1);
+    # G = I/C + 2 J^T J.
+    dims = (1, 1, 1)
+    w1, b1, w2, b2, x, C = 0.4, -0.1, 0.8, 0.2, 0.6, 3.0
+    z1 = 1.0 / (1.0 + math.exp(-(w1 * x + b1)))
+    sp = z1 * (1 - z1)
+    J = np.array([w2 * sp * x, w2 * sp, z1, 1.0])
+    G = np.eye(4) / C + 2.0 * np.outer(J, J)
+    v = np.array([1.0, -2.0, 0.5, 3.0])
+    got = orc.gn_matvec(np.array([w1, b1, w2, b2]), dims, C, np.array([[x]]), v)
+    np.testing.assert_allclose(got, G @ v, rtol=1e-13)
+
+
+# ------------------------------------------------------------------ no hidden layer: ridge regression
+
+def test_no_hidden_layer_newton_step_is_ridge_solution():
+    # z = A x + b is linear in theta, so G is the exact Hessian and one undamped Newton step with
+    # S = all samples lands on the minimiser of f, which for each output u solves
+    # (I/C + (2/l) Xt^T Xt) [a_u; b_u] = (2/l) Xt^T y_u with Xt = [X, 1].
+    dims = (5, 3)
+    cfg, X, Y, theta, _ = _tiny(dims, l=12, s=12, C=2.5)
+    l = X.shape[0]
+    Xt = np.hstack([X, np.ones((l, 1))])
+    H = np.eye(6) / cfg.C + 2.0 / l * Xt.T @ Xt
+    sol = np.linalg.solve(H, 2.0 / l * Xt.T @ Y)           # [6, 3]: column u = [a_u; b_u]
+    theta_star = np.concatenate([sol[:5, :].T.ravel(), sol[5, :]])
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    d, iters, res = orc.cg(theta, dims, cfg.C, X, g, lam=0.0, max_iter=theta.size + 2, sigma=1e-13)
+    np.testing.assert_allclose(theta + d, theta_star, rtol=1e-9, atol=1e-11)
+    g_star, _ = orc.grad(theta_star, dims, cfg.C, X, Y)
+    assert np.linalg.norm(g_star) <= 1e-12 * max(1.0, np.linalg.norm(g))
+
+
+# ------------------------------------------------------------------ CG
+
+@pytest.mark.parametrize("blockdiag", [False, True])
+def test_cg_converges_to_dense_solve(blockdiag):
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims)
+    XS = X[S]
+    lam = 0.3
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    G = tiny_ref.dense_gauss_newton(theta, dims, cfg.C, XS)
+    if blockdiag:
+        G = tiny_ref.zero_offdiag_layer_blocks(G, dims)
+    d_ref = np.linalg.solve(G + lam * np.eye(theta.size), -g)
+    d, iters, res = orc.cg(theta, dims, cfg.C, XS, g, lam, max_iter=4 * theta.size, sigma=1e-12, blockdiag=blockdiag)
+    assert np.linalg.norm(d - d_ref) <= 1e-6 * np.linalg.norm(d_ref)
+    # recurrence residual agrees with the recomputed one
+    prod = orc.gn_matvec_blockdiag if blockdiag else orc.gn_matvec
+    true_res = prod(theta, dims, cfg.C, XS, d) + lam * d + g
+    blocks = orc.block_slices(dims) if blockdiag else [slice(0, theta.size)]
+    assert len(res) == len(blocks)
+    for k, b in enumerate(blocks):
+        assert abs(np.linalg.norm(true_res[b]) - res[k]) <= 1e-6 * np.linalg.norm(g[b])
+        assert res[k] <= 1e-12 * np.linalg.norm(g[b]) * 1.0001
+
+
+def test_cg_first_step_closed_form_and_fixed_iteration_count():
+    cfg = dn_inputs.config(1)
+    X = dn_inputs.make_X(cfg).astype(np.float64)
+    Y = dn_inputs.make_Y(cfg).astype(np.float64)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.3).astype(np.float64)
+    XS = X[dn_inputs.make_subset(cfg)]
+    g, _ = orc.grad(theta, cfg.dims, cfg.C, X, Y)
+    Ag = orc.gn_matvec(theta, cfg.dims, cfg.C, XS, g) + cfg.lam * g
+    d1, it, _ = orc.cg(theta, cfg.dims, cfg.C, XS, g, cfg.lam, max_iter=1)
+    assert it == 1
+    np.testing.assert_allclose(d1, -(g @ g) / (g @ Ag) * g, rtol=1e-12)
+    # sigma = 0 never stops early; iterates decrease the quadratic model monotonically
+    d, it, res, hist = orc.cg(theta, cfg.dims, cfg.C, XS, g, cfg.lam, max_iter=cfg.cg_iters, history=True)
+    assert it == cfg.cg_iters and len(hist) == cfg.cg_iters
+
+    def model(dd):
+        return 0.5 * dd @ (orc.gn_matvec(theta, cfg.dims, cfg.C, XS, dd) + cfg.lam * dd) + g @ dd
+    vals = [model(h) for h in hist]
+    assert all(b < a for a, b in zip(vals, vals[1:]))
+
+
+def test_cg_blockdiag_blocks_stop_independently():
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims)
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    d, iters, res = orc.cg(theta, dims, cfg.C, X[S], g, 0.5, max_iter=200, sigma=1e-3, blockdiag=True)
+    for k, b in enumerate(orc.block_slices(dims)):
+        assert res[k] <= 1e-3 * np.linalg.norm(g[b])
+    # each block equals CG run on that block alone
+    for k, b in enumerate(orc.block_slices(dims)):
+        gk = np.zeros_like(g); gk[b] = g[b]
+        dk, _, _ = orc.cg(theta, dims, cfg.C, X[S], gk, 0.5, max_iter=200, sigma=1e-3, blockdiag=True)
+        np.testing.assert_allclose(d[b], dk[b], rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------------------ inputs
+
+def test_input_generator_shapes_and_ranges():
+    cfg = dn_inputs.config(1)
+    X = dn_inputs.make_X(cfg)
+    assert X.dtype == np.float32 and X.shape == (200, 20) and X.min() >= 0.0 and X.max() < 1.0
+    Y = dn_inputs.make_Y(cfg)
+    assert Y.shape == (200, 4) and np.all(Y.sum(axis=1) == 1.0)
+    S = dn_inputs.make_subset(cfg)
+    assert S.shape == (50,) and len(set(S.tolist())) == 50 and S.min() >= 0 and S.max() < 200
+    th = dn_inputs.make_theta(cfg)
+    assert th.shape == (676,) and cfg.n_params == 676
+    a = math.sqrt(6.0 / 36)
+    assert np.abs(th[:320]).max() <= a and np.all(th[320:336] == 0)
+    np.testing.assert_array_equal(dn_inputs.make_X(cfg, rows=10), X[:10])
+    c4 = dn_inputs.custom((6, 4), l=1000, s=10, features="normal3")
+    X4 = dn_inputs.make_X(c4)
+    assert X4.min() >= -3.0 and X4.max() <= 3.0 and abs(float(X4.mean())) < 0.1
+    assert [dn_inputs.config(i).n_params for i in range(1, 6)] == [676, 328810, 3578510, 12302100, 71222248]
