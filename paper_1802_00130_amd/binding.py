@@ -1,0 +1,201 @@
+"""ctypes binding of libdn.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch is used to own device
+memory and to name the stream.  There is no CPU fallback: if libdn.so is missing or does not
+load, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+DN_FULL = 0
+DN_BLOCKDIAG = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[ctypes.CDLL] = None
+
+_c_float_p = ctypes.c_void_p  # device pointers travel as integers
+
+
+class DnError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        msg = f"{where}: {load_library().dn_strerror(code).decode()} (code {code}"
+        msg += f", hip error {hip})" if hip else ")"
+        super().__init__(msg)
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libdn.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdn.so built in-tree (paper_1802_00130_amd/build.py); raise if it is not there."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not built: run `python -m paper_1802_00130_amd.build` "
+                                "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(path)
+    vp, i, d, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_double, ctypes.c_size_t
+    P = ctypes.POINTER
+    sig = {
+        "dn_strerror": (ctypes.c_char_p, [i]),
+        "dn_create": (i, [P(vp), i, P(i), d, i, i]),
+        "dn_destroy": (None, [vp]),
+        "dn_num_params": (sz, [vp]),
+        "dn_workspace_bytes": (sz, [vp]),
+        "dn_bind": (i, [vp, vp, sz, vp]),
+        "dn_forward": (i, [vp, vp, vp, vp, i, P(d), vp]),
+        "dn_grad": (i, [vp, vp, vp, vp, i, vp, P(d)]),
+        "dn_jacobian_prep": (i, [vp, vp, vp, i, vp, i]),
+        "dn_jacobian_read": (i, [vp, i, vp]),
+        "dn_gn_matvec": (i, [vp, vp, vp, i]),
+        "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
+        "dn_profile_enable": (i, [vp, i]),
+        "dn_profile_reset": (i, [vp]),
+        "dn_profile_num_classes": (i, []),
+        "dn_profile_class_name": (ctypes.c_char_p, [i]),
+        "dn_profile_read": (i, [vp, i, P(d), P(ctypes.c_longlong)]),
+        "dn_last_hip_error": (i, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _LIB = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = (
+    "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_profile_enable",
+    "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
+)
+
+
+def _dev_f32(t: torch.Tensor, name: str, numel: Optional[int] = None) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous float32 device tensor")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name}: expected {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+class Context:
+    """Owns a dn_ctx and the torch tensor that backs its workspace."""
+
+    def __init__(self, dims: Sequence[int], C: float, l_max: int, s_max: int,
+                 device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
+        self._lib = load_library()
+        self.dims = tuple(int(x) for x in dims)
+        self.L = len(self.dims) - 1
+        self._h = ctypes.c_void_p()
+        arr = (ctypes.c_int * len(self.dims))(*self.dims)
+        rc = self._lib.dn_create(ctypes.byref(self._h), self.L, arr, float(C), int(l_max), int(s_max))
+        if rc != 0:
+            raise DnError(rc, "dn_create")
+        self.n = int(self._lib.dn_num_params(self._h))
+        self.device = torch.device(device)
+        self.workspace_bytes = int(self._lib.dn_workspace_bytes(self._h))
+        self.workspace = torch.zeros(self.workspace_bytes // 4 + 64, dtype=torch.float32, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        rc = self._lib.dn_bind(self._h, self._ws_ptr, self.workspace_bytes, self.stream.cuda_stream)
+        self._check(rc, "dn_bind")
+        self.s = 0
+
+    def _check(self, rc: int, where: str) -> None:
+        if rc != 0:
+            raise DnError(rc, where, int(self._lib.dn_last_hip_error(self._h)))
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) and self._h.value:
+            self._lib.dn_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- profiling ---------------------------------------------------------------------------
+    def profile_enable(self, on: bool) -> None:
+        self._check(self._lib.dn_profile_enable(self._h, int(on)), "dn_profile_enable")
+
+    def profile_reset(self) -> None:
+        self._check(self._lib.dn_profile_reset(self._h), "dn_profile_reset")
+
+    def profile_read(self) -> dict:
+        out = {}
+        for k in range(self._lib.dn_profile_num_classes()):
+            ms, cnt = ctypes.c_double(), ctypes.c_longlong()
+            self._check(self._lib.dn_profile_read(self._h, k, ctypes.byref(ms), ctypes.byref(cnt)), "dn_profile_read")
+            out[self._lib.dn_profile_class_name(k).decode()] = (ms.value, cnt.value)
+        return out
+
+
+def dn_forward(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor,
+               ZL: Optional[torch.Tensor] = None) -> float:
+    """f(theta) on all rows of X, Y (Section 2.1 objective)."""
+    l = X.shape[0]
+    f = ctypes.c_double()
+    zl = 0 if ZL is None else _dev_f32(ZL, "ZL", l * ctx.dims[-1])
+    rc = ctx._lib.dn_forward(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
+                             _dev_f32(Y, "Y", l * ctx.dims[-1]), l, ctypes.byref(f), zl)
+    ctx._check(rc, "dn_forward")
+    return f.value
+
+
+def dn_grad(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor, g: torch.Tensor,
+            want_f: bool = True) -> Optional[float]:
+    """g = grad f(theta) (Section 2.2 back-propagation); returns f when want_f."""
+    l = X.shape[0]
+    f = ctypes.c_double()
+    rc = ctx._lib.dn_grad(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
+                          _dev_f32(Y, "Y", l * ctx.dims[-1]), l, _dev_f32(g, "g", ctx.n),
+                          ctypes.byref(f) if want_f else None)
+    ctx._check(rc, "dn_grad")
+    return f.value if want_f else None
+
+
+def dn_jacobian_prep(ctx: Context, theta: torch.Tensor, X: torch.Tensor, S: torch.Tensor) -> None:
+    """Store dz^L/ds^m for the rows S of X (Section 3.3)."""
+    if not (S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()):
+        raise TypeError("S: need a contiguous int32 device tensor")
+    l = X.shape[0]
+    rc = ctx._lib.dn_jacobian_prep(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]), l,
+                                   S.data_ptr(), S.numel())
+    ctx._check(rc, "dn_jacobian_prep")
+    ctx.s = S.numel()
+
+
+def dn_jacobian_read(ctx: Context, m: int, P_out: torch.Tensor) -> None:
+    rc = ctx._lib.dn_jacobian_read(ctx._h, int(m), _dev_f32(P_out, "P_out", ctx.s * ctx.dims[-1] * ctx.dims[m]))
+    ctx._check(rc, "dn_jacobian_read")
+
+
+def dn_gn_matvec(ctx: Context, v: torch.Tensor, out: torch.Tensor, mode: int = DN_FULL) -> None:
+    """out = G^S v, full or per-layer block-diagonal (Sections 4.1-4.3)."""
+    rc = ctx._lib.dn_gn_matvec(ctx._h, _dev_f32(v, "v", ctx.n), _dev_f32(out, "out", ctx.n), int(mode))
+    ctx._check(rc, "dn_gn_matvec")
+
+
+def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int, mode: int,
+          d: torch.Tensor) -> Tuple[int, list]:
+    """CG on (G^S + lam I) d = -g; returns (iterations, residual norms)."""
+    iters = ctypes.c_int()
+    nres = ctx.L if mode == DN_BLOCKDIAG else 1
+    res = (ctypes.c_double * max(nres, 1))()
+    rc = ctx._lib.dn_cg(ctx._h, _dev_f32(g, "g", ctx.n), float(lam), float(sigma), int(max_iter), int(mode),
+                        _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
+    ctx._check(rc, "dn_cg")
+    return iters.value, [res[k] for k in range(nres)]

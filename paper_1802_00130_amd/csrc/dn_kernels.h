@@ -1,0 +1,463 @@
+// Streaming (HBM-bound) kernels of the path: the two passes over the stored Jacobian blocks
+// P^m_i = d z^{L,i} / d s^{m,i}, their fused single-pass form, reductions and CG vector updates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define DN_MAX_LAYERS 8
+#define DN_MAX_WSLOTS 16
+#define DN_MAX_PARTIALS 1024
+
+namespace dn {
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ double wave_sum_d(double x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// Sum of one double per thread over a 256-thread work-group, same order every run.
+// Result valid in every thread.
+__device__ __forceinline__ double block_sum_d(double x, double* lds /* >= 4 doubles */) {
+    x = wave_sum_d(x);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return (lds[0] + lds[1]) + (lds[2] + lds[3]);
+}
+
+// Sum partials[lo..hi) cooperatively (256 threads), fixed order.
+__device__ __forceinline__ double block_sum_range(const double* __restrict__ partials, int lo, int hi, double* lds) {
+    double x = 0.0;
+    for (int i = lo + (int)threadIdx.x; i < hi; i += 256) x += partials[i];
+    return block_sum_d(x, lds);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row gather: XS[i][:] = X[S[i]][:]   (the subsample of Section 4.3)
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ X, const int* __restrict__ S,
+                                                          float* __restrict__ XS, int s, int n0, int l,
+                                                          long long ldx, long long ldxs) {
+    const long long total = (long long)s * n0;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int i = (int)(e / n0);
+        const int t = (int)(e - (long long)i * n0);
+        const int row = min(max(S[i], 0), l - 1);  // ids outside [0, l) are clamped, never dereferenced
+        XS[(long long)i * ldxs + t] = X[(long long)row * ldx + t];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// First stored block (Section 3.3, recursion started from dz^L/dz^L = I):
+//   P^{L-1}_i[u][j] = w^L_{ju} * sigma'(s^{L-1,i}_j),   sigma' = z(1-z).
+// AL is the n_L x n_{L-1} slice of theta for layer L.
+__global__ __launch_bounds__(256) void jac_init_kernel(const float* __restrict__ AL, const float* __restrict__ Z,
+                                                       float* __restrict__ P, int s, int nL, int nh, long long ldz,
+                                                       long long ldp) {
+    const long long total = (long long)s * nL * nh;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int j = (int)(e % nh);
+        const long long iu = e / nh;
+        const int u = (int)(iu % nL);
+        const long long i = iu / nL;
+        const float z = Z[i * ldz + j];
+        P[iu * ldp + j] = AL[(long long)u * nh + j] * (z * (1.0f - z));
+    }
+}
+
+// Dense copy of a stored block (drops the row padding).
+__global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                         long long rows, int cols, long long ld) {
+    const long long total = rows * cols;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const long long rr = e / cols;
+        dst[e] = src[rr * ld + (e - rr * cols)];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Loss partial sums: sum (z - y)^2 in fp64; optionally writes the back-propagation seed
+// 2 (z^L - y)  (Section 3.4) and a dense copy of z^L.
+__global__ __launch_bounds__(256) void loss_delta_kernel(const float* __restrict__ ZL, long long ldz,
+                                                         const float* __restrict__ Y, int l, int nL,
+                                                         float* __restrict__ delta, long long ldd,
+                                                         float* __restrict__ zl_out, double* __restrict__ partials) {
+    __shared__ double red[4];
+    const long long total = (long long)l * nL;
+    double acc = 0.0;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const long long i = e / nL;
+        const int u = (int)(e - i * nL);
+        const float z = ZL[i * ldz + u];
+        const float dlt = z - Y[e];
+        acc += (double)dlt * (double)dlt;
+        if (delta) delta[i * ldd + u] = 2.0f * dlt;
+        if (zl_out) zl_out[e] = z;
+    }
+    acc = block_sum_d(acc, red);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(256) void sumsq_kernel(const float* __restrict__ x, long long n,
+                                                    double* __restrict__ partials) {
+    __shared__ double red[4];
+    double acc = 0.0;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256) {
+        const double v = (double)x[e];
+        acc += v * v;
+    }
+    acc = block_sum_d(acc, red);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+// f = reg / (2C) + loss / l   (Section 2.1 objective)
+__global__ __launch_bounds__(256) void objective_finalize_kernel(const double* __restrict__ loss_partials, int nloss,
+                                                                 const double* __restrict__ reg_partials, int nreg,
+                                                                 double inv2C, double invl, double* __restrict__ f) {
+    __shared__ double red[4];
+    const double a = block_sum_range(loss_partials, 0, nloss, red);
+    const double b = block_sum_range(reg_partials, 0, nreg, red);
+    if (threadIdx.x == 0) *f = b * inv2C + a * invl;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-layer description of the stored blocks and product temporaries for the subsample.
+struct StreamArgs {
+    int L;              // weight layers
+    int s;              // |S|
+    int nL;             // output width
+    int blockdiag;      // 0 full, 1 per-layer
+    int n[DN_MAX_LAYERS + 1];            // n_0..n_L
+    long long ld[DN_MAX_LAYERS + 1];     // row stride of Z/Q/T/P rows of layer m
+    const float* P[DN_MAX_LAYERS + 1];   // P[m], m = 1..L-1: [s][nL][ld[m]]
+    const float* Q[DN_MAX_LAYERS + 1];   // Q[m], m = 1..L: [s][ld[m]]
+    float* T[DN_MAX_LAYERS + 1];         // T[m], m = 1..L: [s][ld[m]]
+    float* R;                            // [L][s][ldr] (full mode uses slot 0 only)
+    long long ldr;
+    // fused kernel: wave w of a work-group owns float4 columns 64*wcol[w] + lane of layer wlayer[w]
+    int nwslots;
+    int wlayer[DN_MAX_WSLOTS];
+    int wcol[DN_MAX_WSLOTS];
+};
+
+// J v, outer sum of Section 4.2: for sample i and output u,
+//   full:       r_i[u]   = q^{L,i}_u + sum_{m<L} sum_j P^m_i[u][j] q^{m,i}_j
+//   per-layer:  r^m_i[u] =                      sum_j P^m_i[u][j] q^{m,i}_j   (m < L),  r^L_i = q^{L,i}
+// Work-group = (sample, block of UB outputs); each wave reduces whole rows of P.
+template <int UB>
+__global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
+    const int ublocks = (a.nL + UB - 1) / UB;
+    const int i = blockIdx.x / ublocks;
+    const int u0 = (blockIdx.x - i * ublocks) * UB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long slab = (long long)a.s * a.ldr;
+    for (int uu = wave; uu < UB; uu += 4) {
+        const int u = u0 + uu;
+        if (u >= a.nL) break;
+        float tot = 0.f;
+        for (int m = 1; m < a.L; ++m) {
+            const int nm4 = a.n[m] >> 2;
+            const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
+            const float* __restrict__ q = a.Q[m] + (long long)i * a.ld[m];
+            float acc = 0.f;
+#pragma unroll 4
+            for (int c = lane; c < nm4; c += 64) {
+                const float4 p4 = *reinterpret_cast<const float4*>(prow + 4 * c);
+                const float4 q4 = *reinterpret_cast<const float4*>(q + 4 * c);
+                acc += p4.x * q4.x + p4.y * q4.y + p4.z * q4.z + p4.w * q4.w;
+            }
+            const int tail = a.n[m] & 3;
+            if (lane < tail) acc += prow[4 * nm4 + lane] * q[4 * nm4 + lane];
+            acc = wave_sum(acc);
+            if (a.blockdiag) {
+                if (lane == 0) a.R[(long long)(m - 1) * slab + (long long)i * a.ldr + u] = acc;
+            } else {
+                tot += acc;
+            }
+        }
+        if (lane == 0) {
+            const float qL = a.Q[a.L][(long long)i * a.ld[a.L] + u];
+            if (a.blockdiag) a.R[(long long)(a.L - 1) * slab + (long long)i * a.ldr + u] = qL;
+            else             a.R[(long long)i * a.ldr + u] = qL + tot;
+        }
+    }
+}
+
+// J^T, inner sum of Section 4.2 with B = 2I:  t^{m,i}_j = sum_u P^m_i[u][j] * 2 r_i[u]  (m < L),
+// t^{L,i} = 2 r_i.  Work-group = (sample, layer, chunk of 1024 columns); threads own 4 columns.
+__global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int chunks_total) {
+    extern __shared__ float rbar[];
+    // decode (sample, layer, chunk): chunk list is layer-major within a sample
+    const int i = blockIdx.x / chunks_total;
+    int c = blockIdx.x - i * chunks_total;
+    int m = 1;
+    for (; m < a.L; ++m) {
+        const int cm = (a.n[m] + 1023) >> 10;
+        if (c < cm) break;
+        c -= cm;
+    }
+    const long long slab = (long long)a.s * a.ldr;
+    if (m == a.L) {
+        // output layer: identity block
+        const float* r = a.R + (a.blockdiag ? (long long)(a.L - 1) * slab : 0) + (long long)i * a.ldr;
+        for (int u = threadIdx.x; u < a.nL; u += 256) a.T[a.L][(long long)i * a.ld[a.L] + u] = 2.0f * r[u];
+        return;
+    }
+    const float* r = a.R + (a.blockdiag ? (long long)(m - 1) * slab : 0) + (long long)i * a.ldr;
+    for (int u = threadIdx.x; u < a.nL; u += 256) rbar[u] = 2.0f * r[u];
+    __syncthreads();
+    const int j = (c << 10) + 4 * threadIdx.x;
+    if (j >= a.n[m]) return;
+    const float* __restrict__ pcol = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // rows are padded to a multiple of 4 floats, so a full float4 is always readable
+#pragma unroll 8
+    for (int u = 0; u < a.nL; ++u) {
+        const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
+        const float w = rbar[u];
+        acc.x += p4.x * w; acc.y += p4.y * w; acc.z += p4.z * w; acc.w += p4.w * w;
+    }
+    float* t = a.T[m] + (long long)i * a.ld[m] + j;
+    *reinterpret_cast<float4*>(t) = acc;
+}
+
+// Both passes in one when n_L <= NLMAX and the hidden widths fit one work-group:
+// one work-group per sample, wave w keeps the 4-column strips of P^m_i (all n_L rows) in
+// registers, so every stored element is read from HBM exactly once per product.
+template <int NLMAX>
+__global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) {
+    __shared__ float part[DN_MAX_WSLOTS][NLMAX];
+    __shared__ float rb[DN_MAX_LAYERS][NLMAX];
+    const int i = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = a.wlayer[wave];
+    const int j = 4 * (64 * a.wcol[wave] + lane);
+    const bool live = j < a.n[m];
+    float4 p[NLMAX];
+    float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* __restrict__ pbase = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
+    if (live) q4 = *reinterpret_cast<const float4*>(a.Q[m] + (long long)i * a.ld[m] + j);
+    // padding columns of Q are never written; mask them
+    if (live) {
+        const int rem = a.n[m] - j;
+        if (rem < 4) { q4.w = 0.f; if (rem < 3) q4.z = 0.f; if (rem < 2) q4.y = 0.f; }
+    }
+#pragma unroll
+    for (int u = 0; u < NLMAX; ++u) {
+        p[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live && u < a.nL) p[u] = *reinterpret_cast<const float4*>(pbase + (long long)u * a.ld[m]);
+    }
+#pragma unroll
+    for (int u = 0; u < NLMAX; ++u) {
+        if (u < a.nL) {
+            float x = p[u].x * q4.x + p[u].y * q4.y + p[u].z * q4.z + p[u].w * q4.w;
+            x = wave_sum(x);
+            if (lane == 0) part[wave][u] = x;
+        }
+    }
+    __syncthreads();
+    {
+        // r (full) or r^m (per layer), doubled: B = 2I
+        const int u = threadIdx.x % NLMAX;
+        const int slot = threadIdx.x / NLMAX;
+        if (u < a.nL) {
+            const float qL = a.Q[a.L][(long long)i * a.ld[a.L] + u];
+            if (!a.blockdiag) {
+                if (slot == 0) {
+                    float rsum = qL;
+                    for (int w = 0; w < a.nwslots; ++w) rsum += part[w][u];
+                    rb[0][u] = 2.0f * rsum;
+                    a.T[a.L][(long long)i * a.ld[a.L] + u] = 2.0f * rsum;
+                }
+            } else if (slot < a.L) {
+                const int mm = slot + 1;
+                if (mm == a.L) {
+                    a.T[a.L][(long long)i * a.ld[a.L] + u] = 2.0f * qL;
+                } else {
+                    float rsum = 0.f;
+                    for (int w = 0; w < a.nwslots; ++w)
+                        if (a.wlayer[w] == mm) rsum += part[w][u];
+                    rb[mm][u] = 2.0f * rsum;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (live) {
+        const float* rr = a.blockdiag ? rb[m] : rb[0];
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < NLMAX; ++u) {
+            if (u < a.nL) {
+                const float w = rr[u];
+                acc.x += p[u].x * w; acc.y += p[u].y * w; acc.z += p[u].z * w; acc.w += p[u].w * w;
+            }
+        }
+        *reinterpret_cast<float4*>(a.T[m] + (long long)i * a.ld[m] + j) = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Final step of every sum over samples: fold the K-slices of the T^T [Z, 1] contraction and add
+// the regularisation term (Section 2.2 gradient; Section 4.3 product):
+//   out[e] = x[e] / C + scale * sum_slices W[slice][j][t]
+// e walks the theta layout; column t = n_{m-1} of W holds the bias sums.
+struct ReduceArgs {
+    int L;
+    int n[DN_MAX_LAYERS + 1];
+    long long off[DN_MAX_LAYERS + 1];   // theta offset of layer m (m = 1..L), off[L+1]... total in ntot
+    long long ntot;
+    const float* W[DN_MAX_LAYERS + 1];  // W[m]: [splits][n_m][ldw[m]]
+    long long ldw[DN_MAX_LAYERS + 1];
+    long long split_stride[DN_MAX_LAYERS + 1];
+    int splits[DN_MAX_LAYERS + 1];
+};
+
+__global__ __launch_bounds__(256) void tn_reduce_kernel(const ReduceArgs a, const float* __restrict__ x,
+                                                        float* __restrict__ out, float invC, float scale) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < a.ntot; e += (long long)gridDim.x * 256) {
+        int m = 1;
+#pragma unroll
+        for (int k = 2; k <= DN_MAX_LAYERS; ++k)
+            if (k <= a.L && e >= a.off[k]) m = k;
+        const long long loc = e - a.off[m];
+        const int np = a.n[m - 1];
+        const long long nw = (long long)np * a.n[m];
+        long long j, t;
+        if (loc < nw) { j = loc / np; t = loc - j * np; }
+        else          { j = loc - nw; t = np; }
+        const float* w = a.W[m] + j * a.ldw[m] + t;
+        float acc = 0.f;
+        for (int sidx = 0; sidx < a.splits[m]; ++sidx) acc += w[(long long)sidx * a.split_stride[m]];
+        out[e] = x[e] * invC + scale * acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Conjugate gradient vector kernels.  The n-vector is cut into segments (one for the full
+// system, one per layer for the block-diagonal systems, Section 4.1); each segment is cut into
+// chunks, one work-group per chunk; dot products are reduced in fp64 in a fixed order.
+struct CgSegs {
+    int nseg;
+    int chunk;                           // elements per work-group
+    long long off[DN_MAX_LAYERS + 1];    // segment k covers [off[k], off[k+1])
+    int cb[DN_MAX_LAYERS + 1];           // first work-group of segment k; cb[nseg] = grid size
+};
+
+struct CgState {                         // lives in device memory, one per iteration parity
+    double rho[DN_MAX_LAYERS];           // r^T r
+    double gnorm2[DN_MAX_LAYERS];        // g^T g
+    int active[DN_MAX_LAYERS];
+    int pad[DN_MAX_LAYERS];
+};
+
+__device__ __forceinline__ void cg_locate(const CgSegs& sg, int& seg, long long& lo, long long& hi) {
+    seg = 0;
+#pragma unroll
+    for (int k = 1; k < DN_MAX_LAYERS; ++k)
+        if (k < sg.nseg && (int)blockIdx.x >= sg.cb[k]) seg = k;
+    lo = sg.off[seg] + (long long)((int)blockIdx.x - sg.cb[seg]) * sg.chunk;
+    hi = lo + sg.chunk;
+    if (hi > sg.off[seg + 1]) hi = sg.off[seg + 1];
+}
+
+// d = 0, r = p = -g, partial g^T g
+__global__ __launch_bounds__(256) void cg_init_kernel(const CgSegs sg, const float* __restrict__ g,
+                                                      float* __restrict__ d, float* __restrict__ r,
+                                                      float* __restrict__ p, double* __restrict__ partials) {
+    __shared__ double red[4];
+    int seg; long long lo, hi;
+    cg_locate(sg, seg, lo, hi);
+    double acc = 0.0;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
+        const float ge = g[e];
+        d[e] = 0.f; r[e] = -ge; p[e] = -ge;
+        acc += (double)ge * (double)ge;
+    }
+    acc = block_sum_d(acc, red);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(256) void cg_init_state_kernel(const CgSegs sg, const double* __restrict__ partials,
+                                                            CgState* __restrict__ st) {
+    __shared__ double red[4];
+    for (int k = 0; k < sg.nseg; ++k) {
+        const double gg = block_sum_range(partials, sg.cb[k], sg.cb[k + 1], red);
+        if (threadIdx.x == 0) {
+            st[0].rho[k] = gg; st[0].gnorm2[k] = gg; st[0].active[k] = gg > 0.0 ? 1 : 0;
+            st[1].rho[k] = gg; st[1].gnorm2[k] = gg; st[1].active[k] = gg > 0.0 ? 1 : 0;
+        }
+    }
+}
+
+// partial p^T (q + lambda p)
+__global__ __launch_bounds__(256) void cg_dot_kernel(const CgSegs sg, const float* __restrict__ p,
+                                                     const float* __restrict__ q, float lambda,
+                                                     double* __restrict__ partials) {
+    __shared__ double red[4];
+    int seg; long long lo, hi;
+    cg_locate(sg, seg, lo, hi);
+    double acc = 0.0;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
+        const float pe = p[e];
+        acc += (double)pe * (double)(q[e] + lambda * pe);
+    }
+    acc = block_sum_d(acc, red);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+// alpha = rho / p^T A p;  d += alpha p;  r -= alpha (q + lambda p);  partial r^T r
+__global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, const CgState* __restrict__ st,
+                                                           const double* __restrict__ pq_partials,
+                                                           const float* __restrict__ p, const float* __restrict__ q,
+                                                           float lambda, float* __restrict__ d, float* __restrict__ r,
+                                                           double* __restrict__ rr_partials) {
+    __shared__ double red[4];
+    int seg; long long lo, hi;
+    cg_locate(sg, seg, lo, hi);
+    if (!st->active[seg]) {
+        if (threadIdx.x == 0) rr_partials[blockIdx.x] = 0.0;
+        return;
+    }
+    const double pq = block_sum_range(pq_partials, sg.cb[seg], sg.cb[seg + 1], red);
+    const float alpha = (float)(st->rho[seg] / pq);
+    double acc = 0.0;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
+        const float pe = p[e];
+        d[e] += alpha * pe;
+        const float re = r[e] - alpha * (q[e] + lambda * pe);
+        r[e] = re;
+        acc += (double)re * (double)re;
+    }
+    acc = block_sum_d(acc, red);
+    if (threadIdx.x == 0) rr_partials[blockIdx.x] = acc;
+}
+
+// rho' = r^T r;  stop test ||r|| <= sigma ||g||;  beta = rho'/rho;  p = r + beta p
+__global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const CgState* __restrict__ st_cur,
+                                                          CgState* __restrict__ st_next,
+                                                          const double* __restrict__ rr_partials, double sigma2,
+                                                          const float* __restrict__ r, float* __restrict__ p) {
+    __shared__ double red[4];
+    int seg; long long lo, hi;
+    cg_locate(sg, seg, lo, hi);
+    const bool first = ((int)blockIdx.x == sg.cb[seg]) && threadIdx.x == 0;
+    if (!st_cur->active[seg]) {
+        if (first) { st_next->rho[seg] = st_cur->rho[seg]; st_next->active[seg] = 0; }
+        return;
+    }
+    const double rho_new = block_sum_range(rr_partials, sg.cb[seg], sg.cb[seg + 1], red);
+    const bool stop = rho_new <= sigma2 * st_cur->gnorm2[seg];
+    if (first) { st_next->rho[seg] = rho_new; st_next->active[seg] = stop ? 0 : 1; }
+    if (stop) return;
+    const float beta = (float)(rho_new / st_cur->rho[seg]);
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) p[e] = r[e] + beta * p[e];
+}
+
+}  // namespace dn

@@ -1,0 +1,805 @@
+// libdn: host side of the C-ABI declared in include/dn.h.  Validates arguments, lays out the
+// caller's workspace, and enqueues the HIP kernels of dn_gemm.h / dn_kernels.h on one stream.
+#include "../../include/dn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dn_gemm.h"
+#include "dn_kernels.h"
+
+using namespace dn;
+
+namespace {
+
+constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
+
+enum KernelClass {
+    KC_GEMM_FWD = 0,      // forward layer products (all samples or subsample)
+    KC_GEMM_BACK,         // back-propagation of delta
+    KC_GEMM_TN_GRAD,      // gradient sums over samples
+    KC_GEMM_PREP,         // Jacobian backward sweeps
+    KC_GEMM_Q,            // product: inner sums over t (Z V)
+    KC_GEMM_TN_MATVEC,    // product: sums over samples (T^T Z)
+    KC_JV_JTV_FUSED,      // product: both passes over P, one read
+    KC_JV,                // product: P q
+    KC_JTV,               // product: P^T r
+    KC_TN_REDUCE,         // slice fold + regularisation term
+    KC_JAC_INIT,
+    KC_GATHER,
+    KC_LOSS,
+    KC_CG_VEC,
+    KC_COUNT
+};
+
+const char* const kClassNames[KC_COUNT] = {
+    "gemm_forward", "gemm_backprop", "gemm_tn_grad", "gemm_jacobian_prep", "gemm_q_matvec", "gemm_tn_matvec",
+    "jv_jtv_fused", "jv_rows", "jtv_cols", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
+
+inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+struct TnPlan {
+    int tile;                       // 64 or 128
+    int splits;
+    int k_per_split;
+    long long floats[DN_MAX_LAYERS + 1];  // per layer, floats of partial storage
+    long long offset[DN_MAX_LAYERS + 1];  // per layer, offset in the partial buffer
+    long long total;
+};
+
+}  // namespace
+
+struct dn_ctx {
+    int L = 0;
+    int dims[DN_MAX_LAYERS + 1] = {0};
+    double C = 1.0;
+    int l_max = 0, s_max = 0;
+    long long n = 0;
+    long long woff[DN_MAX_LAYERS + 1] = {0}, boff[DN_MAX_LAYERS + 1] = {0};
+    long long ld[DN_MAX_LAYERS + 1] = {0};    // padded row stride of layer-m activations
+    long long ldw[DN_MAX_LAYERS + 1] = {0};   // padded row stride of the sum-over-samples partials
+    long long ldr = 0;
+
+    // workspace layout (byte offsets)
+    size_t ws_bytes = 0;
+    size_t o_Zall[DN_MAX_LAYERS + 1] = {0};
+    size_t o_D[2] = {0, 0};
+    size_t o_ZS[DN_MAX_LAYERS + 1] = {0};
+    size_t o_P[DN_MAX_LAYERS + 1] = {0};
+    size_t o_Q[DN_MAX_LAYERS + 1] = {0};
+    size_t o_T[DN_MAX_LAYERS + 1] = {0};
+    size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
+    long long tn_floats = 0;
+
+    char* ws = nullptr;
+    hipStream_t stream = nullptr;
+    bool bound = false;
+    bool prepped = false;
+    int s_cur = 0;
+    int last_hip = 0;
+
+    // profiling
+    bool prof = false;
+    double prof_ms[KC_COUNT] = {0};
+    long long prof_n[KC_COUNT] = {0};
+    struct Pending { int cls; hipEvent_t a, b; };
+    std::vector<Pending> pending;
+    std::vector<hipEvent_t> free_events;
+
+    float* fptr(size_t off) const { return reinterpret_cast<float*>(ws + off); }
+    double* dptr(size_t off) const { return reinterpret_cast<double*>(ws + off); }
+};
+
+namespace {
+
+#define DN_HIP(ctx, expr)                                  \
+    do {                                                   \
+        hipError_t e__ = (expr);                           \
+        if (e__ != hipSuccess) {                           \
+            (ctx)->last_hip = (int)e__;                    \
+            return DN_EHIP;                                \
+        }                                                  \
+    } while (0)
+
+// ---- profiling ---------------------------------------------------------------------------
+
+hipError_t prof_fold(dn_ctx* c) {
+    if (c->pending.empty()) return hipSuccess;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return e;
+    for (auto& p : c->pending) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, p.a, p.b);
+        if (e != hipSuccess) return e;
+        c->prof_ms[p.cls] += ms;
+        c->prof_n[p.cls] += 1;
+        c->free_events.push_back(p.a);
+        c->free_events.push_back(p.b);
+    }
+    c->pending.clear();
+    return hipSuccess;
+}
+
+hipError_t prof_event(dn_ctx* c, hipEvent_t* ev) {
+    if (!c->free_events.empty()) {
+        *ev = c->free_events.back();
+        c->free_events.pop_back();
+        return hipSuccess;
+    }
+    return hipEventCreate(ev);
+}
+
+struct ProfScope {
+    dn_ctx* c;
+    int cls;
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t err = hipSuccess;
+    ProfScope(dn_ctx* ctx, int k) : c(ctx), cls(k) {
+        if (!c->prof) return;
+        if (c->pending.size() >= 4096) err = prof_fold(c);
+        if (err == hipSuccess) err = prof_event(c, &a);
+        if (err == hipSuccess) err = prof_event(c, &b);
+        if (err == hipSuccess) err = hipEventRecord(a, c->stream);
+    }
+    hipError_t end() {
+        if (!c->prof || err != hipSuccess) return err;
+        err = hipEventRecord(b, c->stream);
+        if (err == hipSuccess) c->pending.push_back({cls, a, b});
+        return err;
+    }
+};
+
+// ---- GEMM plumbing -----------------------------------------------------------------------
+
+GemmProblem mk_problem(const float* A, long long lda, const float* B, long long ldb, float* Cc, long long ldc, int M,
+                       int N, int K) {
+    GemmProblem p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = A; p.B = B; p.C = Cc;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.M = M; p.N = N; p.K = K;
+    p.auxdiv = 1;
+    p.splits = 1;
+    p.k_per_split = K;
+    p.a_vec = (aligned16(A) && lda % 4 == 0) ? 1 : 0;
+    p.b_vec = (aligned16(B) && ldb % 4 == 0) ? 1 : 0;
+    return p;
+}
+
+// Fill tile counts / flat tile ranges.  splits applies to every problem of the group.
+void finalize_group(GemmGroup& g, int BM, int BN, int BK, int splits) {
+    int begin = 0;
+    for (int i = 0; i < g.nprob; ++i) {
+        GemmProblem& p = g.p[i];
+        p.tiles_m = cdiv(p.M, BM);
+        p.tiles_n = cdiv(p.N, BN);
+        p.splits = splits;
+        p.k_per_split = (int)round_up(cdiv(p.K, splits), BK);
+        p.tile_begin = begin;
+        begin += p.tiles_m * p.tiles_n * splits;
+    }
+    g.total_tiles = begin;
+}
+
+int group_tiles(const GemmGroup& g, int BM, int BN) {
+    int t = 0;
+    for (int i = 0; i < g.nprob; ++i) t += cdiv(g.p[i].M, BM) * cdiv(g.p[i].N, BN);
+    return t;
+}
+
+template <int BM, int BN, int LA, int LB, int EP>
+hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, 16, 2, 2, LA, LB, EP>), dim3(g.total_tiles), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+template <int LA, int LB, int EP>
+hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
+    if (tile == 128) {
+        finalize_group(g, 128, 128, 16, splits);
+        return launch_gemm_t<128, 128, LA, LB, EP>(g, st);
+    }
+    finalize_group(g, 64, 64, 16, splits);
+    return launch_gemm_t<64, 64, LA, LB, EP>(g, st);
+}
+
+// 128x128 tiles once they alone fill the chip, else 64x64
+int pick_tile(const GemmGroup& g) { return group_tiles(g, 128, 128) >= 256 ? 128 : 64; }
+
+int pick_splits(int tiles, int K) {
+    int s = std::max(1, kTargetWGs / std::max(1, tiles));
+    s = std::min(s, std::max(1, K / 256));
+    return std::min(s, 64);
+}
+
+// Plan of the sums over samples  W_m = T^m^T [Z^{m-1}, 1]  for K samples.  grouped: all layers in
+// one launch (product); otherwise one launch per layer (gradient).
+TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
+    TnPlan pl;
+    std::memset(&pl, 0, sizeof(pl));
+    int t128 = 0, t64 = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        if (!grouped && m != only_layer) continue;
+        t128 += cdiv(c->dims[m], 128) * cdiv(c->dims[m - 1] + 1, 128);
+        t64 += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
+    }
+    pl.tile = t128 >= 256 ? 128 : 64;
+    const int tiles = pl.tile == 128 ? t128 : t64;
+    pl.splits = pick_splits(tiles, K);
+    pl.k_per_split = (int)round_up(cdiv(K, pl.splits), 16);
+    long long off = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        pl.offset[m] = off;
+        pl.floats[m] = (long long)pl.splits * c->dims[m] * c->ldw[m];
+        off += round_up(pl.floats[m], 64);
+    }
+    pl.total = off;
+    return pl;
+}
+
+size_t take(size_t& cur, size_t bytes) {
+    size_t o = cur;
+    cur += (size_t)round_up((long long)bytes, 256);
+    return o;
+}
+
+void layout_workspace(dn_ctx* c) {
+    size_t cur = 0;
+    const int L = c->L;
+    for (int m = 1; m <= L; ++m) c->o_Zall[m] = take(cur, sizeof(float) * (size_t)c->l_max * c->ld[m]);
+    long long ldmax = 0;
+    for (int m = 1; m <= L; ++m) ldmax = std::max(ldmax, c->ld[m]);
+    for (int k = 0; k < 2; ++k) c->o_D[k] = take(cur, sizeof(float) * (size_t)c->l_max * ldmax);
+    for (int m = 0; m <= L; ++m) c->o_ZS[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
+    for (int m = 1; m < L; ++m) c->o_P[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->dims[L] * c->ld[m]);
+    for (int m = 1; m <= L; ++m) c->o_Q[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
+    for (int m = 1; m <= L; ++m) c->o_T[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
+    c->o_R = take(cur, sizeof(float) * (size_t)L * c->s_max * c->ldr);
+    long long tn = plan_tn(c, c->s_max, true, 0).total;
+    for (int m = 1; m <= L; ++m) tn = std::max(tn, plan_tn(c, c->l_max, false, m).total);
+    c->tn_floats = tn;
+    c->o_tn = take(cur, sizeof(float) * (size_t)tn);
+    const size_t nvec = sizeof(float) * (size_t)round_up(c->n, 64);
+    c->o_r = take(cur, nvec);
+    c->o_p = take(cur, nvec);
+    c->o_q = take(cur, nvec);
+    for (int k = 0; k < 3; ++k) c->o_part[k] = take(cur, sizeof(double) * DN_MAX_PARTIALS);
+    c->o_state = take(cur, 2 * sizeof(CgState));
+    c->o_f = take(cur, 256);
+    c->ws_bytes = cur;
+}
+
+int grid_for(long long total, int per_block = 256 * 8) {
+    long long b = (total + per_block - 1) / per_block;
+    return (int)std::max<long long>(1, std::min<long long>(b, 256 * 16));
+}
+
+// ---- forward pass on `rows` rows: Zin -> Z[1..upto] ---------------------------------------
+int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0, int rows, const size_t* o_Z,
+                   int upto) {
+    const float* zin = Z0;
+    long long ldin = ld0;
+    for (int m = 1; m <= upto; ++m) {
+        GemmGroup g;
+        g.nprob = 1;
+        float* zout = c->fptr(o_Z[m]);
+        g.p[0] = mk_problem(zin, ldin, theta + c->woff[m], c->dims[m - 1], zout, c->ld[m], rows, c->dims[m],
+                            c->dims[m - 1]);
+        g.p[0].bias = theta + c->boff[m];
+        const int tile = pick_tile(g);
+        ProfScope ps(c, KC_GEMM_FWD);
+        DN_HIP(c, ps.err);
+        if (m < c->L) DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS_SIGMOID>(g, tile, 1, c->stream)));
+        else          DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+        zin = zout;
+        ldin = c->ld[m];
+    }
+    return DN_OK;
+}
+
+// objective from Z^L of all rows; optionally writes the gradient seed 2(z^L - y)
+int objective(dn_ctx* c, const float* theta, const float* Y, int l, float* delta, long long ldd, float* zl_out,
+              double* f_host) {
+    const int L = c->L;
+    const int nb_loss = std::min(DN_MAX_PARTIALS, grid_for((long long)l * c->dims[L]));
+    const int nb_reg = std::min(DN_MAX_PARTIALS, grid_for(c->n));
+    ProfScope ps(c, KC_LOSS);
+    DN_HIP(c, ps.err);
+    hipLaunchKernelGGL(loss_delta_kernel, dim3(nb_loss), dim3(256), 0, c->stream, c->fptr(c->o_Zall[L]), c->ld[L], Y,
+                       l, c->dims[L], delta, ldd, zl_out, c->dptr(c->o_part[0]));
+    DN_HIP(c, hipGetLastError());
+    if (f_host) {
+        hipLaunchKernelGGL(sumsq_kernel, dim3(nb_reg), dim3(256), 0, c->stream, theta, c->n, c->dptr(c->o_part[1]));
+        DN_HIP(c, hipGetLastError());
+        hipLaunchKernelGGL(objective_finalize_kernel, dim3(1), dim3(256), 0, c->stream, c->dptr(c->o_part[0]),
+                           nb_loss, c->dptr(c->o_part[1]), nb_reg, 1.0 / (2.0 * c->C), 1.0 / (double)l,
+                           c->dptr(c->o_f));
+        DN_HIP(c, hipGetLastError());
+    }
+    DN_HIP(c, ps.end());
+    if (f_host) {
+        DN_HIP(c, hipMemcpyAsync(f_host, c->dptr(c->o_f), sizeof(double), hipMemcpyDeviceToHost, c->stream));
+        DN_HIP(c, hipStreamSynchronize(c->stream));
+    }
+    return DN_OK;
+}
+
+// out = x/C + scale * (folded partial sums), theta layout
+int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan for all */, bool per_layer,
+              const float* x, float* out, double scale) {
+    ReduceArgs ra;
+    std::memset(&ra, 0, sizeof(ra));
+    ra.L = c->L;
+    ra.ntot = c->n;
+    for (int m = 0; m <= c->L; ++m) ra.n[m] = c->dims[m];
+    for (int m = 1; m <= c->L; ++m) {
+        const TnPlan& pl = per_layer ? plans[m] : plans[0];
+        ra.off[m] = c->woff[m];
+        ra.W[m] = c->fptr(c->o_tn) + pl.offset[m];
+        ra.ldw[m] = c->ldw[m];
+        ra.split_stride[m] = (long long)c->dims[m] * c->ldw[m];
+        ra.splits[m] = pl.splits;
+    }
+    ProfScope ps(c, KC_TN_REDUCE);
+    DN_HIP(c, ps.err);
+    hipLaunchKernelGGL(tn_reduce_kernel, dim3(grid_for(c->n, 256 * 4)), dim3(256), 0, c->stream, ra, x, out,
+                       (float)(1.0 / c->C), (float)scale);
+    DN_HIP(c, hipGetLastError());
+    DN_HIP(c, ps.end());
+    return DN_OK;
+}
+
+void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
+    std::memset(&a, 0, sizeof(a));
+    a.L = c->L;
+    a.s = c->s_cur;
+    a.nL = c->dims[c->L];
+    a.blockdiag = mode == DN_BLOCKDIAG ? 1 : 0;
+    for (int m = 0; m <= c->L; ++m) {
+        a.n[m] = c->dims[m];
+        a.ld[m] = c->ld[m];
+    }
+    for (int m = 1; m < c->L; ++m) a.P[m] = c->fptr(c->o_P[m]);
+    for (int m = 1; m <= c->L; ++m) {
+        a.Q[m] = c->fptr(c->o_Q[m]);
+        a.T[m] = c->fptr(c->o_T[m]);
+    }
+    a.R = c->fptr(c->o_R);
+    a.ldr = c->ldr;
+    int w = 0;
+    for (int m = 1; m < c->L; ++m)
+        for (int cidx = 0; cidx < cdiv(c->dims[m], 256); ++cidx, ++w)
+            if (w < DN_MAX_WSLOTS) {
+                a.wlayer[w] = m;
+                a.wcol[w] = cidx;
+            }
+    a.nwslots = w;
+}
+
+// out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
+int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
+    const int L = c->L, s = c->s_cur, nL = c->dims[L];
+    // 1. inner sums over t for every layer: Q^m = Z^{m-1} V^m + vb^m
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            g.p[m - 1] = mk_problem(c->fptr(c->o_ZS[m - 1]), c->ld[m - 1], v + c->woff[m], c->dims[m - 1],
+                                    c->fptr(c->o_Q[m]), c->ld[m], s, c->dims[m], c->dims[m - 1]);
+            g.p[m - 1].bias = v + c->boff[m];
+        }
+        const int tile = pick_tile(g);
+        ProfScope ps(c, KC_GEMM_Q);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 2. the two passes over the stored blocks
+    StreamArgs a;
+    fill_stream_args(c, a, mode);
+    if (L >= 2 && nL <= 16 && a.nwslots <= DN_MAX_WSLOTS) {
+        ProfScope ps(c, KC_JV_JTV_FUSED);
+        DN_HIP(c, ps.err);
+        const dim3 grid(s), block(64 * a.nwslots);
+        if (nL <= 4)       hipLaunchKernelGGL(jv_jtv_fused_kernel<4>, grid, block, 0, c->stream, a);
+        else if (nL <= 8)  hipLaunchKernelGGL(jv_jtv_fused_kernel<8>, grid, block, 0, c->stream, a);
+        else if (nL <= 12) hipLaunchKernelGGL(jv_jtv_fused_kernel<12>, grid, block, 0, c->stream, a);
+        else               hipLaunchKernelGGL(jv_jtv_fused_kernel<16>, grid, block, 0, c->stream, a);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    } else {
+        {
+            ProfScope ps(c, KC_JV);
+            DN_HIP(c, ps.err);
+            constexpr int UB = 16;
+            hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+        {
+            ProfScope ps(c, KC_JTV);
+            DN_HIP(c, ps.err);
+            int chunks = 1;
+            for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 1024);
+            hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
+                               sizeof(float) * nL, c->stream, a, chunks);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+    }
+    // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1]
+    TnPlan pl = plan_tn(c, s, true, 0);
+    if (pl.total > c->tn_floats) return DN_ENOSPC;
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            GemmProblem& p = g.p[m - 1];
+            p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]), c->ld[m - 1],
+                           c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
+            p.b_ones_col = 1;
+            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+        }
+        ProfScope ps(c, KC_GEMM_TN_MATVEC);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<RC, RC, EP_STORE>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 4. fold slices, scale by 1/|S|, add v/C
+    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s);
+}
+
+void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
+    std::memset(&sg, 0, sizeof(sg));
+    if (mode == DN_BLOCKDIAG) {
+        sg.nseg = c->L;
+        for (int m = 1; m <= c->L; ++m) sg.off[m - 1] = c->woff[m];
+        sg.off[c->L] = c->n;
+    } else {
+        sg.nseg = 1;
+        sg.off[0] = 0;
+        sg.off[1] = c->n;
+    }
+    // chunk size: at most ~512 work-groups in total, at least 2048 elements each
+    long long chunk = std::max<long long>(2048, round_up((c->n + 511) / 512, 1024));
+    for (;;) {
+        long long tot = 0;
+        for (int k = 0; k < sg.nseg; ++k) tot += (sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk;
+        if (tot <= DN_MAX_PARTIALS) break;
+        chunk *= 2;
+    }
+    sg.chunk = (int)chunk;
+    int b = 0;
+    for (int k = 0; k < sg.nseg; ++k) {
+        sg.cb[k] = b;
+        b += (int)((sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk);
+    }
+    sg.cb[sg.nseg] = b;
+}
+
+bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG; }
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char* dn_strerror(int code) {
+    switch (code) {
+        case DN_OK: return "ok";
+        case DN_EINVAL: return "invalid argument";
+        case DN_ENOSPC: return "workspace too small";
+        case DN_ESTATE: return "call out of order (no workspace bound, or no Jacobian prepared)";
+        case DN_EHIP: return "HIP runtime error";
+        case DN_ENOMEM: return "host allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_max) {
+    if (!out) return DN_EINVAL;
+    *out = nullptr;
+    if (!dims || L < 1 || L > DN_MAX_LAYERS || !(C > 0.0) || l_max < 1 || s_max < 1) return DN_EINVAL;
+    for (int m = 0; m <= L; ++m)
+        if (dims[m] < 1) return DN_EINVAL;
+    // row counts of the batched sweeps are int: s_max * n_L rows
+    if ((long long)s_max * dims[L] > 0x7fffffffLL) return DN_EINVAL;
+    dn_ctx* c = new (std::nothrow) dn_ctx();
+    if (!c) return DN_ENOMEM;
+    c->L = L;
+    c->C = C;
+    c->l_max = l_max;
+    c->s_max = s_max;
+    long long o = 0;
+    for (int m = 0; m <= L; ++m) {
+        c->dims[m] = dims[m];
+        c->ld[m] = round_up(dims[m], 4);
+        if (m >= 1) {
+            c->woff[m] = o;
+            o += (long long)dims[m - 1] * dims[m];
+            c->boff[m] = o;
+            o += dims[m];
+            c->ldw[m] = round_up(dims[m - 1] + 1, 4);
+        }
+    }
+    c->n = o;
+    c->ldr = round_up(dims[L], 4);
+    layout_workspace(c);
+    *out = c;
+    return DN_OK;
+}
+
+void dn_destroy(dn_ctx* c) {
+    if (!c) return;
+    for (auto& p : c->pending) {
+        (void)hipEventDestroy(p.a);
+        (void)hipEventDestroy(p.b);
+    }
+    for (auto e : c->free_events) (void)hipEventDestroy(e);
+    delete c;
+}
+
+size_t dn_num_params(const dn_ctx* c) { return c ? (size_t)c->n : 0; }
+size_t dn_workspace_bytes(const dn_ctx* c) { return c ? c->ws_bytes : 0; }
+int dn_last_hip_error(const dn_ctx* c) { return c ? c->last_hip : 0; }
+
+int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
+    if (!c || !d_workspace) return DN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0) return DN_EINVAL;
+    if (bytes < c->ws_bytes) return DN_ENOSPC;
+    c->ws = static_cast<char*>(d_workspace);
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->bound = true;
+    c->prepped = false;
+    return DN_OK;
+}
+
+int dn_forward(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, double* f_host, float* ZL) {
+    if (!c || !theta || !X || !Y || !f_host || l < 1 || l > c->l_max) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    int rc = forward_layers(c, theta, X, c->dims[0], l, c->o_Zall, c->L);
+    if (rc != DN_OK) return rc;
+    return objective(c, theta, Y, l, nullptr, 0, ZL, f_host);
+}
+
+int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, float* g, double* f_host) {
+    if (!c || !theta || !X || !Y || !g || l < 1 || l > c->l_max) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    const int L = c->L;
+    int rc = forward_layers(c, theta, X, c->dims[0], l, c->o_Zall, L);
+    if (rc != DN_OK) return rc;
+    // seed 2 (z^L - y) into D[0]
+    int cur = 0;
+    rc = objective(c, theta, Y, l, c->fptr(c->o_D[cur]), c->ld[L], nullptr, f_host);
+    if (rc != DN_OK) return rc;
+    TnPlan plans[DN_MAX_LAYERS + 1];
+    // partial buffers of different layers must not overlap: give each layer its own range
+    long long tn_off = 0;
+    for (int m = 1; m <= L; ++m) {
+        plans[m] = plan_tn(c, l, false, m);
+        plans[m].offset[m] = tn_off;
+        tn_off += round_up(plans[m].floats[m], 64);
+    }
+    if (tn_off > c->tn_floats) {
+        // fall back to one slice per layer, which always fits
+        tn_off = 0;
+        for (int m = 1; m <= L; ++m) {
+            plans[m].splits = 1;
+            plans[m].k_per_split = (int)round_up(l, 16);
+            plans[m].floats[m] = (long long)c->dims[m] * c->ldw[m];
+            plans[m].offset[m] = tn_off;
+            tn_off += round_up(plans[m].floats[m], 64);
+        }
+        if (tn_off > c->tn_floats) return DN_ENOSPC;
+    }
+    for (int m = L; m >= 1; --m) {
+        const float* delta = c->fptr(c->o_D[cur]);
+        const float* zprev = (m == 1) ? X : c->fptr(c->o_Zall[m - 1]);
+        const long long ldprev = (m == 1) ? c->dims[0] : c->ld[m - 1];
+        {
+            // sum over samples: delta^m^T [z^{m-1}, 1]
+            GemmGroup g1;
+            g1.nprob = 1;
+            GemmProblem& p = g1.p[0];
+            p = mk_problem(delta, c->ld[m], zprev, ldprev, c->fptr(c->o_tn) + plans[m].offset[m], c->ldw[m],
+                           c->dims[m], c->dims[m - 1] + 1, l);
+            p.b_ones_col = 1;
+            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+            ProfScope ps(c, KC_GEMM_TN_GRAD);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<RC, RC, EP_STORE>(g1, plans[m].tile, plans[m].splits, c->stream)));
+            DN_HIP(c, ps.end());
+        }
+        if (m > 1) {
+            // delta^{m-1} = (delta^m (W^m)^T) * z^{m-1} (1 - z^{m-1})
+            GemmGroup g2;
+            g2.nprob = 1;
+            GemmProblem& p = g2.p[0];
+            p = mk_problem(delta, c->ld[m], theta + c->woff[m], c->dims[m - 1], c->fptr(c->o_D[cur ^ 1]),
+                           c->ld[m - 1], l, c->dims[m - 1], c->dims[m]);
+            p.aux = zprev;
+            p.ldaux = ldprev;
+            p.auxdiv = 1;
+            const int tile = pick_tile(g2);
+            ProfScope ps(c, KC_GEMM_BACK);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g2, tile, 1, c->stream)));
+            DN_HIP(c, ps.end());
+            cur ^= 1;
+        }
+    }
+    return tn_reduce(c, plans, true, theta, g, 1.0 / (double)l);
+}
+
+int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const int* S, int s) {
+    if (!c || !theta || !X || !S || l < 1 || s < 1 || s > c->s_max) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    const int L = c->L, nL = c->dims[L];
+    c->prepped = false;
+    {
+        ProfScope ps(c, KC_GATHER);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for((long long)s * c->dims[0])), dim3(256), 0, c->stream, X,
+                           S, c->fptr(c->o_ZS[0]), s, c->dims[0], l, (long long)c->dims[0], c->ld[0]);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // z^{m,i} for the hidden layers (the output layer's activations are not needed by the products)
+    int rc = forward_layers(c, theta, c->fptr(c->o_ZS[0]), c->ld[0], s, c->o_ZS, L - 1);
+    if (rc != DN_OK) return rc;
+    if (L >= 2) {
+        ProfScope ps(c, KC_JAC_INIT);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(jac_init_kernel, dim3(grid_for((long long)s * nL * c->dims[L - 1])), dim3(256), 0,
+                           c->stream, theta + c->woff[L], c->fptr(c->o_ZS[L - 1]), c->fptr(c->o_P[L - 1]), s, nL,
+                           c->dims[L - 1], c->ld[L - 1], c->ld[L - 1]);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // P^{m-1} = (P^m (W^m)^T) * sigma'(s^{m-1}):  the n_L backward sweeps of all samples as one product
+    for (int m = L - 1; m >= 2; --m) {
+        GemmGroup g;
+        g.nprob = 1;
+        GemmProblem& p = g.p[0];
+        p = mk_problem(c->fptr(c->o_P[m]), c->ld[m], theta + c->woff[m], c->dims[m - 1], c->fptr(c->o_P[m - 1]),
+                       c->ld[m - 1], s * nL, c->dims[m - 1], c->dims[m]);
+        p.aux = c->fptr(c->o_ZS[m - 1]);
+        p.ldaux = c->ld[m - 1];
+        p.auxdiv = nL;
+        const int tile = pick_tile(g);
+        ProfScope ps(c, KC_GEMM_PREP);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    c->s_cur = s;
+    c->prepped = true;
+    return DN_OK;
+}
+
+int dn_jacobian_read(dn_ctx* c, int m, float* P_out) {
+    if (!c || !P_out || m < 1 || m >= c->L) return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    const long long rows = (long long)c->s_cur * c->dims[c->L];
+    hipLaunchKernelGGL(unpad_rows_kernel, dim3(grid_for(rows * c->dims[m])), dim3(256), 0, c->stream,
+                       c->fptr(c->o_P[m]), P_out, rows, c->dims[m], c->ld[m]);
+    DN_HIP(c, hipGetLastError());
+    return DN_OK;
+}
+
+int dn_gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
+    if (!c || !v || !out || bad_mode(mode)) return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    return gn_matvec(c, v, out, mode);
+}
+
+int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, float* d, int* iters_host,
+          double* resnorm_host) {
+    if (!c || !g || !d || !iters_host || !resnorm_host || bad_mode(mode) || max_iter < 1 || !(lambda >= 0.0) ||
+        !(sigma >= 0.0))
+        return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    CgSegs sg;
+    build_segs(c, mode, sg);
+    const int grid = sg.cb[sg.nseg];
+    float* r = c->fptr(c->o_r);
+    float* p = c->fptr(c->o_p);
+    float* q = c->fptr(c->o_q);
+    double* part0 = c->dptr(c->o_part[0]);
+    double* part1 = c->dptr(c->o_part[1]);
+    double* part2 = c->dptr(c->o_part[2]);
+    CgState* st = reinterpret_cast<CgState*>(c->ws + c->o_state);
+    CgState hst;
+    {
+        ProfScope ps(c, KC_CG_VEC);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(cg_init_kernel, dim3(grid), dim3(256), 0, c->stream, sg, g, d, r, p, part0);
+        DN_HIP(c, hipGetLastError());
+        hipLaunchKernelGGL(cg_init_state_kernel, dim3(1), dim3(256), 0, c->stream, sg, part0, st);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    DN_HIP(c, hipMemcpyAsync(&hst, st, sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    auto any_active = [&](const CgState& s) {
+        for (int k = 0; k < sg.nseg; ++k)
+            if (s.active[k]) return true;
+        return false;
+    };
+    int iters = 0;
+    bool active = any_active(hst);
+    while (iters < max_iter && active) {
+        int rc = gn_matvec(c, p, q, mode);
+        if (rc != DN_OK) return rc;
+        const CgState* cur = st + (iters & 1);
+        CgState* nxt = st + ((iters + 1) & 1);
+        {
+            ProfScope ps(c, KC_CG_VEC);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(cg_dot_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda, part1);
+            DN_HIP(c, hipGetLastError());
+            hipLaunchKernelGGL(cg_update_dr_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, part1, p, q,
+                               (float)lambda, d, r, part2);
+            DN_HIP(c, hipGetLastError());
+            hipLaunchKernelGGL(cg_update_p_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, nxt, part2,
+                               sigma * sigma, r, p);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+        ++iters;
+        if (sigma > 0.0) {
+            DN_HIP(c, hipMemcpyAsync(&hst, nxt, sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
+            DN_HIP(c, hipStreamSynchronize(c->stream));
+            active = any_active(hst);
+        }
+    }
+    DN_HIP(c, hipMemcpyAsync(&hst, st + (iters & 1), sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    *iters_host = iters;
+    for (int k = 0; k < sg.nseg; ++k) resnorm_host[k] = std::sqrt(hst.rho[k]);
+    return DN_OK;
+}
+
+int dn_profile_enable(dn_ctx* c, int on) {
+    if (!c) return DN_EINVAL;
+    if (!on && c->prof) DN_HIP(c, prof_fold(c));
+    c->prof = on != 0;
+    return DN_OK;
+}
+
+int dn_profile_reset(dn_ctx* c) {
+    if (!c) return DN_EINVAL;
+    DN_HIP(c, prof_fold(c));
+    for (int k = 0; k < KC_COUNT; ++k) {
+        c->prof_ms[k] = 0.0;
+        c->prof_n[k] = 0;
+    }
+    return DN_OK;
+}
+
+int dn_profile_num_classes(void) { return KC_COUNT; }
+
+const char* dn_profile_class_name(int which) {
+    return (which >= 0 && which < KC_COUNT) ? kClassNames[which] : nullptr;
+}
+
+int dn_profile_read(dn_ctx* c, int which, double* total_ms_host, long long* launches_host) {
+    if (!c || which < 0 || which >= KC_COUNT || !total_ms_host || !launches_host) return DN_EINVAL;
+    DN_HIP(c, prof_fold(c));
+    *total_ms_host = c->prof_ms[which];
+    *launches_host = c->prof_n[which];
+    return DN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,45 @@
+"""Helpers for the GPU parity tests: put a seeded workload on the device and run the oracle beside it."""
+import numpy as np
+import torch
+
+import dn_inputs
+import paper_1802_00130_amd as dn
+from oracle import dn_oracle as orc
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+class Workload:
+    def __init__(self, cfg, bias_scale=0.0, rows=None):
+        self.cfg = cfg
+        self.X = dn_inputs.make_X(cfg, rows)
+        self.Y = dn_inputs.make_Y(cfg, rows)
+        self.theta = dn_inputs.make_theta(cfg, bias_scale=bias_scale)
+        self.S = dn_inputs.make_subset(cfg, rows)
+        self.l = self.X.shape[0]
+        self.s = self.S.shape[0]
+        dev = torch.device("cuda:0")
+        self.dX = torch.from_numpy(self.X).to(dev)
+        self.dY = torch.from_numpy(self.Y).to(dev)
+        self.dtheta = torch.from_numpy(self.theta).to(dev)
+        self.dS = torch.from_numpy(self.S).to(dev)
+        self.ctx = dn.Context(cfg.dims, cfg.C, self.l, self.s)
+        self.n = self.ctx.n
+
+    def dev(self, a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:0")
+
+    def empty(self):
+        return torch.empty(self.n, dtype=torch.float32, device="cuda:0")
+
+    @property
+    def XS64(self):
+        return self.X[self.S].astype(np.float64)
+
+    def oracle_matvec(self, v, blockdiag=False):
+        f = orc.gn_matvec_blockdiag if blockdiag else orc.gn_matvec
+        return f(self.theta.astype(np.float64), self.cfg.dims, self.cfg.C, self.XS64, v.astype(np.float64))
