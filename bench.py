@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the subsampled Gauss-Newton path on one MI355X.
+
+One step = one pass of the whole path on a synthetic workload already resident in HBM:
+dn_forward (f), dn_grad, dn_jacobian_prep, `mv_reps` x dn_gn_matvec (full), `mv_reps` x
+dn_gn_matvec (per-layer block-diagonal), dn_cg (full) and dn_cg (block-diagonal) with the
+configuration's CG iteration count.  Prints ONE JSON line:
+
+  value        Gauss-Newton matvecs/s = full products per second inside the timed steps
+               (HIP events around the `mv_reps` back-to-back full products of every step)
+  ms_per_step  wall time of the whole step
+  roofline     the dominant kernel of dn_gn_matvec: algorithmic flops (or bytes) per launch over
+               its mean duration, measured with HIP events inside the same timed steps
+  cpu_baseline the fp64 oracle's product rate on the host cores, on the same workload
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
+
+
+def work_per_launch(cfg, s):
+    """Algorithmic work of one launch of each product kernel class (Section 4.2 / Section 5.2 costs).
+
+    GEMM classes: 2 flops per multiply-add of the |T_{m-1}| x |T_m| term summed over layers.
+    Streaming classes: bytes of the stored blocks that one launch must read once.
+    """
+    d = cfg.dims
+    L = len(d) - 1
+    wsum = sum(d[m - 1] * d[m] for m in range(1, L + 1))
+    hid = sum(d[m] for m in range(1, L))
+    pbytes = 4.0 * s * d[L] * hid
+    return {
+        "gemm_q_matvec": ("mfma", 2.0 * s * wsum),
+        "gemm_tn_matvec": ("mfma", 2.0 * s * wsum),
+        "jv_jtv_fused": ("hbm", pbytes),
+        "jv_rows": ("hbm", pbytes),
+        "jtv_cols": ("hbm", pbytes),
+        "tn_reduce": ("hbm", 4.0 * 3 * cfg.n_params),
+    }
+
+
+def matvec_flops(cfg, s):
+    d = cfg.dims
+    L = len(d) - 1
+    return s * (4.0 * sum(d[m - 1] * d[m] for m in range(1, L + 1)) + 4.0 * d[L] * sum(d[m] for m in range(1, L)))
+
+
+def cpu_baseline(cfg, X, theta, S, budget_s=15.0):
+    """Time the oracle's full product on the host; bounded by `budget_s` seconds of work."""
+    import numpy as np
+    from oracle import dn_oracle as orc
+    import dn_inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    XS = X[S].astype(np.float64)
+    th = theta.astype(np.float64)
+    v = dn_inputs.make_probe(cfg, 0).astype(np.float64)
+    orc.gn_matvec(th, cfg.dims, cfg.C, XS, v)      # warm-up (BLAS thread start-up)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        orc.gn_matvec(th, cfg.dims, cfg.C, XS, v)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 20:
+            break
+    return {"value": reps / el, "unit": "matvecs/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{reps} full G^S v products, same theta/X_S/v as the GPU run (|S|={XS.shape[0]}), numpy fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE configuration 1..5 (default 2)")
+    ap.add_argument("--mv-reps", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import dn_inputs
+    import paper_1802_00130_amd as dn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    cfg = dn_inputs.config(args.config)
+    dev = torch.device("cuda:0")
+    X = dn_inputs.make_X(cfg)
+    Y = dn_inputs.make_Y(cfg)
+    theta = dn_inputs.make_theta(cfg)
+    S = dn_inputs.make_subset(cfg)
+    v = dn_inputs.make_probe(cfg, 0)
+    dX, dY = torch.from_numpy(X).to(dev), torch.from_numpy(Y).to(dev)
+    dtheta, dS, dv = torch.from_numpy(theta).to(dev), torch.from_numpy(S).to(dev), torch.from_numpy(v).to(dev)
+    ctx = dn.Context(cfg.dims, cfg.C, cfg.l, cfg.s)
+    n = ctx.n
+    g = torch.empty(n, dtype=torch.float32, device=dev)
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    d = torch.empty(n, dtype=torch.float32, device=dev)
+    R = args.mv_reps
+
+    phases = ["forward", "grad", "jacobian_prep", "matvec_full", "matvec_blockdiag", "cg_full", "cg_blockdiag"]
+
+    def step(ev=None):
+        def mark(k):
+            if ev is not None:
+                ev[k].record()
+        mark(0)
+        dn.dn_forward(ctx, dtheta, dX, dY)
+        mark(1)
+        dn.dn_grad(ctx, dtheta, dX, dY, g, want_f=False)
+        mark(2)
+        dn.dn_jacobian_prep(ctx, dtheta, dX, dS)
+        mark(3)
+        for _ in range(R):
+            dn.dn_gn_matvec(ctx, dv, out, dn.DN_FULL)
+        mark(4)
+        for _ in range(R):
+            dn.dn_gn_matvec(ctx, dv, out, dn.DN_BLOCKDIAG)
+        mark(5)
+        dn.dn_cg(ctx, g, cfg.lam, 0.0, cfg.cg_iters, dn.DN_FULL, d)
+        mark(6)
+        dn.dn_cg(ctx, g, cfg.lam, 0.0, cfg.cg_iters, dn.DN_BLOCKDIAG, d)
+        mark(7)
+
+    # warm-up, with every kernel class bracketed once to find the dominant product kernel
+    work = work_per_launch(cfg, cfg.s)
+    ctx.profile_select(None)
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    dominant = max(work, key=lambda k: prof.get(k, (0.0, 0))[0])
+    ctx.profile_select([dominant])
+    ctx.profile_reset()
+
+    # timed region
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+
+    phase_ms = {p: 0.0 for p in phases}
+    for evs in events:
+        for i, p in enumerate(phases):
+            phase_ms[p] += evs[i].elapsed_time(evs[i + 1])
+    for p in phases:
+        phase_ms[p] /= args.steps
+    mv_ms = phase_ms["matvec_full"] / R
+    value = 1000.0 / mv_ms
+    ms_per_step = wall * 1000.0 / args.steps
+
+    bound, unit_work = work[dominant]
+    tot_ms, launches = prof[dominant]
+    avg_ms = tot_ms / max(1, launches)
+    if bound == "mfma":
+        achieved = unit_work / (avg_ms * 1e-3) / 1e12
+        peak, unit = PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
+    else:
+        achieved = unit_work / (avg_ms * 1e-3) / 1e9
+        peak, unit = PEAK_HBM_GBS, "GB/s"
+    roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": None, "avg_kernel_ms": avg_ms, "launches": int(launches),
+                "work_per_launch": unit_work}
+
+    mv_tflops = matvec_flops(cfg, cfg.s) / (mv_ms * 1e-3) / 1e12
+    res = {
+        "metric": "Gauss-Newton matvecs/sec and achieved fp32-MFMA TFLOP/s, 1xMI355X",
+        "value": value, "unit": "matvecs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "dims": list(cfg.dims), "l": cfg.l, "subsample": cfg.s, "C": cfg.C,
+                   "lambda": cfg.lam, "cg_iters": cfg.cg_iters, "mv_reps": R, "seed": cfg.seed},
+        "matvec_ms": mv_ms, "matvec_blockdiag_ms": phase_ms["matvec_blockdiag"] / R,
+        "matvec_tflops": mv_tflops, "matvec_frac_of_fp32_mfma_peak": mv_tflops / PEAK_FP32_MFMA_TFLOPS,
+        "cg_ms_per_iteration": phase_ms["cg_full"] / cfg.cg_iters,
+        "phase_ms": phase_ms,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, X, theta, S)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -138,6 +138,8 @@ int dn_cg(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter
  * number of launches since the last dn_profile_reset.  Reading synchronises the stream.
  */
 int dn_profile_enable(dn_ctx* ctx, int on);
+/* Restrict the bracketing to the kernel classes whose bit is set (bit k = class k); default all. */
+int dn_profile_select(dn_ctx* ctx, unsigned long long class_mask);
 int dn_profile_reset(dn_ctx* ctx);
 int dn_profile_num_classes(void);
 const char* dn_profile_class_name(int which);

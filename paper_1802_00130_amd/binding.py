@@ -59,6 +59,7 @@ def load_library() -> ctypes.CDLL:
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
         "dn_profile_enable": (i, [vp, i]),
+        "dn_profile_select": (i, [vp, ctypes.c_ulonglong]),
         "dn_profile_reset": (i, [vp]),
         "dn_profile_num_classes": (i, []),
         "dn_profile_class_name": (ctypes.c_char_p, [i]),
@@ -76,6 +77,7 @@ def load_library() -> ctypes.CDLL:
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
     "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_profile_enable",
+    "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
 )
 
@@ -130,6 +132,14 @@ class Context:
     # -- profiling ---------------------------------------------------------------------------
     def profile_enable(self, on: bool) -> None:
         self._check(self._lib.dn_profile_enable(self._h, int(on)), "dn_profile_enable")
+
+    def profile_select(self, names=None) -> None:
+        """Bracket only the named kernel classes (None = all)."""
+        mask = 0
+        for k in range(self._lib.dn_profile_num_classes()):
+            if names is None or self._lib.dn_profile_class_name(k).decode() in names:
+                mask |= 1 << k
+        self._check(self._lib.dn_profile_select(self._h, mask), "dn_profile_select")
 
     def profile_reset(self) -> None:
         self._check(self._lib.dn_profile_reset(self._h), "dn_profile_reset")

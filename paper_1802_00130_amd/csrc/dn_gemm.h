@@ -17,6 +17,10 @@
 // The k values handled by the two lane halves are any fixed pairing as long as A and B agree;
 // here within each group of 8 consecutive k the half h takes k = 4h + j for step j = 0..3,
 // which lets a K-contiguous operand be fetched from LDS with one 128-bit read per 4 MFMAs.
+//
+// Pipeline: PF K-tiles are in flight in registers ahead of the tile being multiplied; LDS is
+// double-buffered; one barrier per K-tile.  The steady-state loop touches only whole K-tiles and
+// has no range checks on k; the ragged last tile goes through a checked loader.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,6 +30,8 @@
 namespace dn {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// four floats that are only known to be 4-byte aligned
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 
 enum OperandLayout { KC = 0, RC = 1 };
 
@@ -50,8 +56,8 @@ struct GemmProblem {
     int splits;          // number of K-slices (>= 1)
     int k_per_split;     // multiple of the K tile
     int tile_begin;      // first flat tile id of this problem
-    int a_vec, b_vec;    // 1 if 16-byte vector loads are legal for the operand
-    int b_ones_col;      // 1: column N-1 of op(B) is a virtual column of ones (not read from memory)
+    int b_ones_col;      // 1: column N-1 of op(B) is a virtual column of ones (not read from memory);
+                         //    only for a row-contiguous B
 };
 
 struct GemmGroup {
@@ -64,54 +70,117 @@ __device__ __forceinline__ float sigmoidf_fast(float s) { return 1.0f / (1.0f + 
 
 // ---- global -> register tile fetch -------------------------------------------------------
 // A tile of an operand is ROWS x BK values.  KC: slot = (row, 4 consecutive k).
-// RC: slot = (k, 4 consecutive rows).  Out-of-range elements are zero.
+// RC: slot = (k, 4 consecutive rows).  Out-of-range elements are zero.  The per-slot address and
+// row validity are fixed for the whole K loop and computed once in init().
+// Slot modes: 0 nothing to read (zero), 1 four-wide load, 2 element-wise load with row checks,
+//             4 four-wide load from a clamped (valid) address; the values land in rows of the tile
+//               that lie outside the matrix and never reach memory.
 template <int ROWS, int BK, int LAYOUT, int NT>
 struct TileFetch {
     static constexpr int SLOTS = ROWS * BK / 4;
-    static constexpr int PER_THREAD = (SLOTS + NT - 1) / NT;
-    float4 v[PER_THREAD];
+    static_assert(SLOTS % NT == 0, "every thread owns whole fetch slots");
+    static constexpr int PER_THREAD = SLOTS / NT;
+    // LDS strides: KC rows are BK+4 floats apart, RC k-rows are ROWS+8 floats apart.
+    static constexpr int LDS_STRIDE = (LAYOUT == KC) ? (BK + 4) : (ROWS + 8);
+    static constexpr int LDS_FLOATS = (LAYOUT == KC) ? ROWS * (BK + 4) : BK * (ROWS + 8);
 
-    __device__ __forceinline__ void load(const float* __restrict__ base, long long ld, int row0, int k0,
-                                         int rows_total, int k_end, int vec_ok, int ones_row, int tid) {
+    struct Addr {
+        const float* p[PER_THREAD];   // KC: &op[row][4*kq]; RC: &op[0][row]
+        int q[PER_THREAD];            // KC: 4*kq (k offset inside the tile); RC: k row inside the tile
+        int mode[PER_THREAD];
+        int rem[PER_THREAD];          // RC mode 2: valid rows counted from this slot's first row
+        int ones_at[PER_THREAD];      // RC mode 2: position (0..3) of the virtual ones row, else -1
+        long long ld;
+    };
+
+    __device__ static __forceinline__ void init(Addr& a, const float* __restrict__ base, long long ld, int row0,
+                                                int rows_total, int ones_row, int tid) {
+        a.ld = ld;
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
-            int s = tid + i * NT;
+            const int s = tid + i * NT;
+            a.mode[i] = 0; a.p[i] = base; a.q[i] = 0; a.rem[i] = 0; a.ones_at[i] = -1;
+            if (LAYOUT == KC) {
+                const int row = row0 + s / (BK / 4);
+                a.q[i] = 4 * (s % (BK / 4));
+                // rows past the end read the last valid row
+                const int rr = row < rows_total ? row : rows_total - 1;
+                a.p[i] = base + (long long)rr * ld + a.q[i];
+                a.mode[i] = row < rows_total ? 1 : 4;
+            } else {
+                const int row = row0 + 4 * (s % (ROWS / 4));
+                a.q[i] = s / (ROWS / 4);
+                const int real_rows = ones_row >= 0 ? rows_total - 1 : rows_total;  // rows that exist in memory
+                if (row + 3 < real_rows) {
+                    a.p[i] = base + row;
+                    a.mode[i] = 1;
+                } else if (row < rows_total) {
+                    a.p[i] = base + row;
+                    a.rem[i] = rows_total - row;
+                    if (ones_row >= row && ones_row <= row + 3) a.ones_at[i] = ones_row - row;
+                    a.mode[i] = 2;
+                } else if (real_rows >= 4) {
+                    a.p[i] = base;          // any valid address; result discarded
+                    a.mode[i] = 4;
+                }
+            }
+        }
+    }
+
+    float4 v[PER_THREAD];
+
+    __device__ __forceinline__ void rc_elements(const Addr& a, int i, const float* p, float4& x) const {
+        if (a.rem[i] > 0) x.x = (a.ones_at[i] == 0) ? 1.f : p[0];
+        if (a.rem[i] > 1) x.y = (a.ones_at[i] == 1) ? 1.f : p[1];
+        if (a.rem[i] > 2) x.z = (a.ones_at[i] == 2) ? 1.f : p[2];
+        if (a.rem[i] > 3) x.w = (a.ones_at[i] == 3) ? 1.f : p[3];
+    }
+
+    // Tile lies entirely below k_end: no k checks.  Vector loads only assume 4-byte alignment
+    // (f32x4u); the compiler picks the widest access the target allows for that.
+    __device__ __forceinline__ void load_full(const Addr& a, int k0) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (SLOTS % NT == 0 || s < SLOTS) {
-                if (LAYOUT == KC) {
-                    int row = row0 + s / (BK / 4);
-                    int k = k0 + 4 * (s % (BK / 4));
-                    if (row < rows_total) {
-                        if (row == ones_row) {
-                            x.x = (k + 0 < k_end) ? 1.f : 0.f;
-                            x.y = (k + 1 < k_end) ? 1.f : 0.f;
-                            x.z = (k + 2 < k_end) ? 1.f : 0.f;
-                            x.w = (k + 3 < k_end) ? 1.f : 0.f;
-                        } else {
-                            const float* p = base + (long long)row * ld + k;
-                            if (vec_ok && k + 3 < k_end) {
-                                x = *reinterpret_cast<const float4*>(p);
-                            } else {
-                                if (k + 0 < k_end) x.x = p[0];
-                                if (k + 1 < k_end) x.y = p[1];
-                                if (k + 2 < k_end) x.z = p[2];
-                                if (k + 3 < k_end) x.w = p[3];
-                            }
-                        }
-                    }
-                } else {
-                    int k = k0 + s / (ROWS / 4);
-                    int row = row0 + 4 * (s % (ROWS / 4));
-                    if (k < k_end) {
-                        const float* p = base + (long long)k * ld + row;
-                        if (vec_ok && row + 3 < rows_total && (ones_row < row || ones_row > row + 3)) {
-                            x = *reinterpret_cast<const float4*>(p);
-                        } else {
-                            if (row + 0 < rows_total) x.x = (row + 0 == ones_row) ? 1.f : p[0];
-                            if (row + 1 < rows_total) x.y = (row + 1 == ones_row) ? 1.f : p[1];
-                            if (row + 2 < rows_total) x.z = (row + 2 == ones_row) ? 1.f : p[2];
-                            if (row + 3 < rows_total) x.w = (row + 3 == ones_row) ? 1.f : p[3];
-                        }
+            if (LAYOUT == KC) {
+                const f32x4u t = *reinterpret_cast<const f32x4u*>(a.p[i] + k0);
+                x = make_float4(t[0], t[1], t[2], t[3]);
+            } else {
+                const float* p = a.p[i] + (long long)(k0 + a.q[i]) * a.ld;
+                if (a.mode[i] == 1 || a.mode[i] == 4) {
+                    const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
+                    x = make_float4(t[0], t[1], t[2], t[3]);
+                } else if (a.mode[i] == 2) {
+                    rc_elements(a, i, p, x);
+                }
+            }
+            v[i] = x;
+        }
+    }
+
+    // Last, partial K tile: every element is checked against k_end.
+    __device__ __forceinline__ void load_tail(const Addr& a, int k0, int k_end) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (LAYOUT == KC) {
+                const int k = k0 + a.q[i];
+                const float* p = a.p[i] + k0;
+                if (a.mode[i] == 1) {
+                    if (k + 0 < k_end) x.x = p[0];
+                    if (k + 1 < k_end) x.y = p[1];
+                    if (k + 2 < k_end) x.z = p[2];
+                    if (k + 3 < k_end) x.w = p[3];
+                }
+            } else {
+                const int k = k0 + a.q[i];
+                if (k < k_end) {
+                    const float* p = a.p[i] + (long long)k * a.ld;
+                    if (a.mode[i] == 1) {
+                        const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
+                        x = make_float4(t[0], t[1], t[2], t[3]);
+                    } else if (a.mode[i] == 2) {
+                        rc_elements(a, i, p, x);
                     }
                 }
             }
@@ -119,20 +188,16 @@ struct TileFetch {
         }
     }
 
-    // LDS strides: KC rows are BK+4 floats apart, RC k-rows are ROWS+8 floats apart.
-    static constexpr int LDS_STRIDE = (LAYOUT == KC) ? (BK + 4) : (ROWS + 8);
-    static constexpr int LDS_FLOATS = (LAYOUT == KC) ? ROWS * (BK + 4) : BK * (ROWS + 8);
-
-    __device__ __forceinline__ void store(float* lds, int tid) const {
+    // Slots of mode 4 carry the values of some other, valid row.  They only ever feed output rows
+    // (or columns) beyond M (or N), which the epilogue never writes, so they need no zeroing.
+    __device__ __forceinline__ void store(const Addr& a, float* lds, int tid) const {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
-            int s = tid + i * NT;
-            if (SLOTS % NT == 0 || s < SLOTS) {
-                int off;
-                if (LAYOUT == KC) off = (s / (BK / 4)) * LDS_STRIDE + 4 * (s % (BK / 4));
-                else              off = (s / (ROWS / 4)) * LDS_STRIDE + 4 * (s % (ROWS / 4));
-                *reinterpret_cast<float4*>(lds + off) = v[i];
-            }
+            const int s = tid + i * NT;
+            int off;
+            if (LAYOUT == KC) off = (s / (BK / 4)) * LDS_STRIDE + 4 * (s % (BK / 4));
+            else              off = (s / (ROWS / 4)) * LDS_STRIDE + 4 * (s % (ROWS / 4));
+            *reinterpret_cast<float4*>(lds + off) = v[i];
         }
     }
 };
@@ -153,13 +218,15 @@ __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int
 }
 
 // BM x BN macro tile, 4 waves arranged WGM x WGN, each wave owning (BM/WGM) x (BN/WGN).
-template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int EP>
+// PF = number of K tiles kept in flight in registers ahead of the one being multiplied.
+template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int EP, int PF>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     constexpr int NT = 256;
     static_assert(WGM * WGN == 4, "four waves per work-group");
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / 32, FN = WN / 32;
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
+    static_assert(PF == 2 || PF == 4, "prefetch depth must be even so LDS buffer parity is static");
     using FetchA = TileFetch<BM, BK, LA, NT>;
     using FetchB = TileFetch<BN, BK, LB, NT>;
 
@@ -189,8 +256,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     const int r = lane & 31, h = lane >> 5;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
 
-    const float* __restrict__ Ab = P.A;
-    const float* __restrict__ Bb = P.B;
     const int ones_row = P.b_ones_col ? (P.N - 1) : -1;
 
     f32x16 acc[FM][FN];
@@ -201,24 +266,24 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    FetchA fa;
-    FetchB fb;
-    const int nk = (k_end - k_begin + BK - 1) / BK;
-    if (nk > 0) {
-        fa.load(Ab, P.lda, m0, k_begin, P.M, k_end, P.a_vec, -1, tid);
-        fb.load(Bb, P.ldb, n0, k_begin, P.N, k_end, P.b_vec, ones_row, tid);
-        fa.store(ldsA[0], tid);
-        fb.store(ldsB[0], tid);
-    }
-    __syncthreads();
+    typename FetchA::Addr aa;
+    typename FetchB::Addr ab;
+    FetchA::init(aa, P.A, P.lda, m0, P.M, -1, tid);
+    FetchB::init(ab, P.B, P.ldb, n0, P.N, ones_row, tid);
+    FetchA fa[PF];
+    FetchB fb[PF];
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            const int k0 = k_begin + (kt + 1) * BK;
-            fa.load(Ab, P.lda, m0, k0, P.M, k_end, P.a_vec, -1, tid);
-            fb.load(Bb, P.ldb, n0, k0, P.N, k_end, P.b_vec, ones_row, tid);
-        }
+    const int klen = max(k_end - k_begin, 0);
+    const int nfull = klen / BK;                    // whole K tiles
+    const int nk = nfull + ((klen - nfull * BK) > 0 ? 1 : 0);
+
+    auto fetch = [&](int slot, int kt) {
+        // kt < nk is guaranteed by the callers
+        const int k0 = k_begin + kt * BK;
+        if (kt < nfull) { fa[slot].load_full(aa, k0); fb[slot].load_full(ab, k0); }
+        else            { fa[slot].load_tail(aa, k0, k_end); fb[slot].load_tail(ab, k0, k_end); }
+    };
+    auto multiply = [&](int cur) {
 #pragma unroll
         for (int kk = 0; kk < BK / 8; ++kk) {
             float af[FM][4], bf[FN][4];
@@ -227,18 +292,65 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
             for (int j = 0; j < FN; ++j) frag_read<BN, BK, LB>(ldsB[cur], wn0 + j * 32 + r, kk, h, bf[j]);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][s], bf[j][s], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][s4], bf[j][s4], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) {
-            fa.store(ldsA[cur ^ 1], tid);
-            fb.store(ldsB[cur ^ 1], tid);
+    };
+
+    // prologue: tiles 0..PF-1 into registers, tile 0 into LDS
+    if (nfull >= PF) {
+        // common case, kept free of the checked loader so the PF tiles are issued back to back
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            fa[u].load_full(aa, k_begin + u * BK);
+            fb[u].load_full(ab, k_begin + u * BK);
         }
-        __syncthreads();
+    } else {
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (u < nk) fetch(u, u);
+    }
+    if (nk > 0) {
+        fa[0].store(aa, ldsA[0], tid);
+        fb[0].store(ab, ldsB[0], tid);
+    }
+    __syncthreads();
+
+    int kt0 = 0;
+    // steady state: every refill in this round is a whole tile (kt0 + PF-1 + PF < nfull)
+    for (; kt0 + 2 * PF <= nfull; kt0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int kt = kt0 + u;
+            // register slot u held tile kt, which already sits in LDS: refill it with tile kt + PF
+            const int k0 = k_begin + (kt + PF) * BK;
+            fa[u].load_full(aa, k0);
+            fb[u].load_full(ab, k0);
+            multiply(u & 1);                 // u & 1 == kt & 1 because PF is even
+            fa[(u + 1) % PF].store(aa, ldsA[(u & 1) ^ 1], tid);
+            fb[(u + 1) % PF].store(ab, ldsB[(u & 1) ^ 1], tid);
+            __syncthreads();
+        }
+    }
+    // drain: refills stop at nk, the last tile may be ragged
+    for (; kt0 < nk; kt0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int kt = kt0 + u;
+            if (kt < nk) {
+                if (kt + PF < nk) fetch(u, kt + PF);
+                multiply(u & 1);
+                if (kt + 1 < nk) {
+                    fa[(u + 1) % PF].store(aa, ldsA[(u & 1) ^ 1], tid);
+                    fb[(u + 1) % PF].store(ab, ldsB[(u & 1) ^ 1], tid);
+                }
+                __syncthreads();
+            }
+        }
     }
 
     // ---- epilogue: lane holds column n = .. + r and rows 8*(e/4) + 4*h + e%4 of each 32x32 block ----

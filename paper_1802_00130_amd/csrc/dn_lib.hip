@@ -20,6 +20,10 @@ using namespace dn;
 namespace {
 
 constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
+// K-tile depth and register prefetch depth of the two macro-tile shapes
+constexpr int kBK64 = 16, kPF64 = 4;
+constexpr int kBK128 = 16, kPF128 = 2;
+constexpr int kBKmax = 32;
 
 enum KernelClass {
     KC_GEMM_FWD = 0,      // forward layer products (all samples or subsample)
@@ -89,6 +93,7 @@ struct dn_ctx {
 
     // profiling
     bool prof = false;
+    unsigned long long prof_mask = ~0ull;
     double prof_ms[KC_COUNT] = {0};
     long long prof_n[KC_COUNT] = {0};
     struct Pending { int cls; hipEvent_t a, b; };
@@ -143,15 +148,17 @@ struct ProfScope {
     int cls;
     hipEvent_t a = nullptr, b = nullptr;
     hipError_t err = hipSuccess;
+    bool on = false;
     ProfScope(dn_ctx* ctx, int k) : c(ctx), cls(k) {
-        if (!c->prof) return;
+        on = c->prof && ((c->prof_mask >> k) & 1ull);
+        if (!on) return;
         if (c->pending.size() >= 4096) err = prof_fold(c);
         if (err == hipSuccess) err = prof_event(c, &a);
         if (err == hipSuccess) err = prof_event(c, &b);
         if (err == hipSuccess) err = hipEventRecord(a, c->stream);
     }
     hipError_t end() {
-        if (!c->prof || err != hipSuccess) return err;
+        if (!on || err != hipSuccess) return err;
         err = hipEventRecord(b, c->stream);
         if (err == hipSuccess) c->pending.push_back({cls, a, b});
         return err;
@@ -170,8 +177,6 @@ GemmProblem mk_problem(const float* A, long long lda, const float* B, long long 
     p.auxdiv = 1;
     p.splits = 1;
     p.k_per_split = K;
-    p.a_vec = (aligned16(A) && lda % 4 == 0) ? 1 : 0;
-    p.b_vec = (aligned16(B) && ldb % 4 == 0) ? 1 : 0;
     return p;
 }
 
@@ -196,25 +201,28 @@ int group_tiles(const GemmGroup& g, int BM, int BN) {
     return t;
 }
 
-template <int BM, int BN, int LA, int LB, int EP>
+template <int BM, int BN, int BK, int PF, int LA, int LB, int EP>
 hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     if (g.total_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, 16, 2, 2, LA, LB, EP>), dim3(g.total_tiles), dim3(256), 0, st, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, EP, PF>), dim3(g.total_tiles), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
 template <int LA, int LB, int EP>
 hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
     if (tile == 128) {
-        finalize_group(g, 128, 128, 16, splits);
-        return launch_gemm_t<128, 128, LA, LB, EP>(g, st);
+        finalize_group(g, 128, 128, kBK128, splits);
+        return launch_gemm_t<128, 128, kBK128, kPF128, LA, LB, EP>(g, st);
     }
-    finalize_group(g, 64, 64, 16, splits);
-    return launch_gemm_t<64, 64, LA, LB, EP>(g, st);
+    finalize_group(g, 64, 64, kBK64, splits);
+    return launch_gemm_t<64, 64, kBK64, kPF64, LA, LB, EP>(g, st);
 }
 
-// 128x128 tiles once they alone fill the chip, else 64x64
-int pick_tile(const GemmGroup& g) { return group_tiles(g, 128, 128) >= 256 ? 128 : 64; }
+// Measured on MI355X: 64x64 tiles win on every shape of the path except large products with both
+// operands K-contiguous, where 128x128 tiles are ~6% faster once there are >= 4 of them per CU.
+int pick_tile(const GemmGroup& g, bool both_k_contiguous) {
+    return (both_k_contiguous && group_tiles(g, 128, 128) >= 1024) ? 128 : 64;
+}
 
 int pick_splits(int tiles, int K) {
     int s = std::max(1, kTargetWGs / std::max(1, tiles));
@@ -227,16 +235,14 @@ int pick_splits(int tiles, int K) {
 TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
     TnPlan pl;
     std::memset(&pl, 0, sizeof(pl));
-    int t128 = 0, t64 = 0;
+    int tiles = 0;
     for (int m = 1; m <= c->L; ++m) {
         if (!grouped && m != only_layer) continue;
-        t128 += cdiv(c->dims[m], 128) * cdiv(c->dims[m - 1] + 1, 128);
-        t64 += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
+        tiles += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
     }
-    pl.tile = t128 >= 256 ? 128 : 64;
-    const int tiles = pl.tile == 128 ? t128 : t64;
+    pl.tile = 64;
     pl.splits = pick_splits(tiles, K);
-    pl.k_per_split = (int)round_up(cdiv(K, pl.splits), 16);
+    pl.k_per_split = (int)round_up(cdiv(K, pl.splits), kBKmax);
     long long off = 0;
     for (int m = 1; m <= c->L; ++m) {
         pl.offset[m] = off;
@@ -296,7 +302,7 @@ int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0
         g.p[0] = mk_problem(zin, ldin, theta + c->woff[m], c->dims[m - 1], zout, c->ld[m], rows, c->dims[m],
                             c->dims[m - 1]);
         g.p[0].bias = theta + c->boff[m];
-        const int tile = pick_tile(g);
+        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_FWD);
         DN_HIP(c, ps.err);
         if (m < c->L) DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS_SIGMOID>(g, tile, 1, c->stream)));
@@ -341,8 +347,8 @@ int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan fo
     ReduceArgs ra;
     std::memset(&ra, 0, sizeof(ra));
     ra.L = c->L;
-    ra.ntot = c->n;
     for (int m = 0; m <= c->L; ++m) ra.n[m] = c->dims[m];
+    int blocks = 0;
     for (int m = 1; m <= c->L; ++m) {
         const TnPlan& pl = per_layer ? plans[m] : plans[0];
         ra.off[m] = c->woff[m];
@@ -350,11 +356,15 @@ int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan fo
         ra.ldw[m] = c->ldw[m];
         ra.split_stride[m] = (long long)c->dims[m] * c->ldw[m];
         ra.splits[m] = pl.splits;
+        ra.chunks[m] = cdiv(c->dims[m - 1] + 1, 1024);
+        ra.blk_begin[m] = blocks;
+        blocks += c->dims[m] * ra.chunks[m];
     }
+    ra.blk_begin[c->L + 1] = blocks;
     ProfScope ps(c, KC_TN_REDUCE);
     DN_HIP(c, ps.err);
-    hipLaunchKernelGGL(tn_reduce_kernel, dim3(grid_for(c->n, 256 * 4)), dim3(256), 0, c->stream, ra, x, out,
-                       (float)(1.0 / c->C), (float)scale);
+    hipLaunchKernelGGL(tn_reduce_kernel, dim3(blocks), dim3(256), 0, c->stream, ra, x, out, (float)(1.0 / c->C),
+                       (float)scale);
     DN_HIP(c, hipGetLastError());
     DN_HIP(c, ps.end());
     return DN_OK;
@@ -399,7 +409,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
                                     c->fptr(c->o_Q[m]), c->ld[m], s, c->dims[m], c->dims[m - 1]);
             g.p[m - 1].bias = v + c->boff[m];
         }
-        const int tile = pick_tile(g);
+        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_Q);
         DN_HIP(c, ps.err);
         DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS>(g, tile, 1, c->stream)));
@@ -596,7 +606,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
         tn_off = 0;
         for (int m = 1; m <= L; ++m) {
             plans[m].splits = 1;
-            plans[m].k_per_split = (int)round_up(l, 16);
+            plans[m].k_per_split = (int)round_up(l, kBKmax);
             plans[m].floats[m] = (long long)c->dims[m] * c->ldw[m];
             plans[m].offset[m] = tn_off;
             tn_off += round_up(plans[m].floats[m], 64);
@@ -631,7 +641,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             p.aux = zprev;
             p.ldaux = ldprev;
             p.auxdiv = 1;
-            const int tile = pick_tile(g2);
+            const int tile = pick_tile(g2, false);
             ProfScope ps(c, KC_GEMM_BACK);
             DN_HIP(c, ps.err);
             DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g2, tile, 1, c->stream)));
@@ -677,7 +687,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         p.aux = c->fptr(c->o_ZS[m - 1]);
         p.ldaux = c->ld[m - 1];
         p.auxdiv = nL;
-        const int tile = pick_tile(g);
+        const int tile = pick_tile(g, false);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
         DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g, tile, 1, c->stream)));
@@ -775,6 +785,13 @@ int dn_profile_enable(dn_ctx* c, int on) {
     if (!c) return DN_EINVAL;
     if (!on && c->prof) DN_HIP(c, prof_fold(c));
     c->prof = on != 0;
+    return DN_OK;
+}
+
+int dn_profile_select(dn_ctx* c, unsigned long long class_mask) {
+    if (!c) return DN_EINVAL;
+    DN_HIP(c, prof_fold(c));
+    c->prof_mask = class_mask;
     return DN_OK;
 }
 

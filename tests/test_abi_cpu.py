@@ -1,0 +1,82 @@
+"""CPU-only checks of the C-ABI: the library loads, exports what include/dn.h declares, and validates
+arguments on the host before touching a device (no compute is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1802_00130_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_1802_00130_amd import build
+        build.build_lib(verbose=False)
+    return binding.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dn_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert "dn_gn_matvec" in names and "dn_cg" in names and len(names) >= 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def _create(lib, dims, C=1.0, l=100, s=10):
+    h = ctypes.c_void_p()
+    arr = (ctypes.c_int * len(dims))(*dims)
+    rc = lib.dn_create(ctypes.byref(h), len(dims) - 1, arr, C, l, s)
+    return rc, h
+
+
+def test_create_validation_and_sizes(lib):
+    rc, h = _create(lib, (784, 300, 300, 10), l=60000, s=3000)
+    assert rc == 0 and lib.dn_num_params(h) == 328810
+    # workspace holds at least the stored blocks |S| n_L sum_{m<L} n_m and the activations for l rows
+    need = 4 * (3000 * 10 * 600 + 60000 * 610)
+    assert lib.dn_workspace_bytes(h) >= need
+    lib.dn_destroy(h)
+    assert _create(lib, (4, 0, 2))[0] == -1
+    assert _create(lib, (4, 2), C=0.0)[0] == -1
+    assert _create(lib, (4, 2), l=0)[0] == -1
+    assert _create(lib, (4,))[0] == -1
+    assert _create(lib, tuple([3] * 11))[0] == -1
+    assert lib.dn_create(None, 1, (ctypes.c_int * 2)(2, 2), 1.0, 1, 1) == -1
+    assert lib.dn_num_params(None) == 0 and lib.dn_workspace_bytes(None) == 0
+
+
+def test_call_order_and_argument_errors(lib):
+    rc, h = _create(lib, (6, 5, 3))
+    assert rc == 0
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
+    f = ctypes.c_double()
+    it = ctypes.c_int()
+    assert lib.dn_forward(h, fake, fake, fake, 10, ctypes.byref(f), None) == -3      # not bound
+    assert lib.dn_bind(h, None, 1 << 30, None) == -1
+    assert lib.dn_bind(h, ctypes.c_void_p(0x1001), 1 << 30, None) == -1              # misaligned
+    assert lib.dn_bind(h, fake, 16, None) == -2                                      # too small
+    assert lib.dn_bind(h, fake, lib.dn_workspace_bytes(h), None) == 0
+    assert lib.dn_forward(h, None, fake, fake, 10, ctypes.byref(f), None) == -1
+    assert lib.dn_forward(h, fake, fake, fake, 101, ctypes.byref(f), None) == -1     # l > l_max
+    assert lib.dn_grad(h, fake, fake, fake, 0, fake, None) == -1
+    assert lib.dn_jacobian_prep(h, fake, fake, 100, fake, 11) == -1                  # s > s_max
+    assert lib.dn_gn_matvec(h, fake, fake, 0) == -3                                  # no Jacobian prepared
+    assert lib.dn_gn_matvec(h, fake, fake, 5) == -1
+    assert lib.dn_cg(h, fake, 1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
+    assert lib.dn_cg(h, fake, -1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_jacobian_read(h, 2, fake) == -1
+    assert lib.dn_jacobian_read(h, 1, fake) == -3
+    assert lib.dn_strerror(-2).decode() == "workspace too small"
+    assert lib.dn_profile_num_classes() >= 10 and lib.dn_profile_class_name(0).decode() == "gemm_forward"
+    lib.dn_destroy(h)

@@ -1,0 +1,91 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch shapes bench.py times.
+
+Configuration 2 (the benchmarked one) and 3 are checked whole: f, gradient, both products, 10 CG
+iterations.  Configurations 4 and 5 check both products whole (every entry of G v against the oracle), 10 CG
+iterations of the full system, and f and the gradient on the first 20000 rows (the oracle's gradient over
+all l rows of those two takes many minutes on the host); DN_TEST_LIGHT=1 skips their CG and
+block-diagonal legs.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import dn_inputs
+import paper_1802_00130_amd as dn
+from oracle import dn_oracle as orc
+from tests.gpu_common import Workload, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+TOL_CG = 1e-3
+HEAVY = os.environ.get("DN_TEST_LIGHT", "0") != "1"
+
+
+def _check_products(w, modes=(dn.DN_FULL, dn.DN_BLOCKDIAG)):
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    v = dn_inputs.make_probe(w.cfg, 0)
+    dv = w.dev(v)
+    for mode in modes:
+        out = w.empty()
+        dn.dn_gn_matvec(w.ctx, dv, out, mode)
+        ref = w.oracle_matvec(v, blockdiag=(mode == dn.DN_BLOCKDIAG))
+        err = rel_l2(out.cpu().numpy(), ref)
+        print(f"[{w.cfg.name}] mode {mode}: rel err {err:.2e}", flush=True)
+        assert err <= TOL
+        again = w.empty()
+        dn.dn_gn_matvec(w.ctx, dv, again, mode)
+        assert torch.equal(out, again)
+
+
+def _check_grad(w):
+    cfg = w.cfg
+    g = w.empty()
+    f = dn.dn_grad(w.ctx, w.dtheta, w.dX, w.dY, g)
+    g_ref, f_ref = orc.grad(w.theta.astype(np.float64), cfg.dims, cfg.C, w.X.astype(np.float64),
+                            w.Y.astype(np.float64))
+    f2 = dn.dn_forward(w.ctx, w.dtheta, w.dX, w.dY)
+    print(f"[{cfg.name}] f {f:.8f} ref {f_ref:.8f}; grad rel err {rel_l2(g.cpu().numpy(), g_ref):.2e}", flush=True)
+    assert abs(f - f_ref) <= TOL * abs(f_ref) and abs(f2 - f_ref) <= TOL * abs(f_ref)
+    assert rel_l2(g.cpu().numpy(), g_ref) <= TOL
+    return g_ref
+
+
+def _check_cg(w, g_ref, modes, iters=10):
+    cfg = w.cfg
+    th = w.theta.astype(np.float64)
+    g32 = g_ref.astype(np.float32)
+    for mode in modes:
+        d = w.empty()
+        it, res = dn.dn_cg(w.ctx, w.dev(g32), cfg.lam, 0.0, iters, mode, d)
+        d_ref, it_ref, res_ref = orc.cg(th, cfg.dims, cfg.C, w.XS64, g32.astype(np.float64), cfg.lam, iters,
+                                        blockdiag=(mode == dn.DN_BLOCKDIAG))
+        err = rel_l2(d.cpu().numpy(), d_ref)
+        print(f"[{cfg.name}] cg mode {mode}: {it} iterations, rel err {err:.2e}", flush=True)
+        assert it == it_ref == iters
+        assert err <= TOL_CG
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_full_configuration(idx):
+    w = Workload(dn_inputs.config(idx))
+    g_ref = _check_grad(w)
+    _check_products(w)
+    _check_cg(w, g_ref, (dn.DN_FULL, dn.DN_BLOCKDIAG))
+    w.ctx.close()
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_large_configuration(idx):
+    cfg = dn_inputs.config(idx)
+    # gradient parity on a prefix of the samples (the oracle's full-l gradient takes many minutes);
+    # the subsample S is drawn from that prefix, with the configuration's full |S|
+    w = Workload(cfg, rows=20000)
+    assert w.s == cfg.s
+    g_ref = _check_grad(w)
+    _check_products(w, modes=(dn.DN_FULL, dn.DN_BLOCKDIAG) if (idx == 4 or HEAVY) else (dn.DN_FULL,))
+    if HEAVY:
+        _check_cg(w, g_ref, (dn.DN_FULL,))
+    w.ctx.close()
