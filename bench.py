@@ -154,6 +154,7 @@ def main():
         step()
     torch.cuda.synchronize()
     prof = ctx.profile_read()
+    warm_kernel_ms = {k: (ms / cnt if cnt else 0.0) for k, (ms, cnt) in prof.items() if cnt}
     dominant = max(work, key=lambda k: prof.get(k, (0.0, 0))[0])
     ctx.profile_select([dominant])
     ctx.profile_reset()
@@ -204,6 +205,7 @@ def main():
         "matvec_tflops": mv_tflops, "matvec_frac_of_fp32_mfma_peak": mv_tflops / PEAK_FP32_MFMA_TFLOPS,
         "cg_ms_per_iteration": phase_ms["cg_full"] / cfg.cg_iters,
         "phase_ms": phase_ms,
+        "warmup_avg_kernel_ms": warm_kernel_ms,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

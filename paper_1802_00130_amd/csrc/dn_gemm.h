@@ -320,9 +320,35 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     }
     __syncthreads();
 
+    // Long contractions are summed in segments of kFlushTiles K-tiles: the MFMA accumulator is folded
+    // into a second fp32 accumulator and cleared, which shortens the chains of dependent fp32 roundings
+    // (error grows with the square root of the chain length).
+    f32x16 acc2[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc2[i][j][e] = 0.f;
+    constexpr int kFlushTiles = 512 / BK;
+    int since_flush = 0;
+
     int kt0 = 0;
     // steady state: every refill in this round is a whole tile (kt0 + PF-1 + PF < nfull)
     for (; kt0 + 2 * PF <= nfull; kt0 += PF) {
+        if (since_flush >= kFlushTiles) {
+            since_flush = 0;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        acc2[i][j][e] += acc[i][j][e];
+                        acc[i][j][e] = 0.f;
+                    }
+        }
+        since_flush += PF;
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int kt = kt0 + u;
@@ -367,7 +393,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
             for (int e = 0; e < 16; ++e) {
                 const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
                 if (m >= P.M) continue;
-                float x = acc[i][j][e];
+                float x = acc[i][j][e] + acc2[i][j][e];
                 if (EP == EP_BIAS) x += bias;
                 if (EP == EP_BIAS_SIGMOID) x = sigmoidf_fast(x + bias);
                 if (EP == EP_DSIGMOID) {

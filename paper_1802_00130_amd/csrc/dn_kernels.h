@@ -160,23 +160,24 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
     for (int uu = wave; uu < UB; uu += 4) {
         const int u = u0 + uu;
         if (u >= a.nL) break;
-        float tot = 0.f;
+        // the pass is bound by HBM, so the sums are carried in fp64 at no cost in time
+        double tot = 0.0;
         for (int m = 1; m < a.L; ++m) {
             const int nm4 = a.n[m] >> 2;
             const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
             const float* __restrict__ q = a.Q[m] + (long long)i * a.ld[m];
-            float acc = 0.f;
+            double acc = 0.0;
 #pragma unroll 4
             for (int c = lane; c < nm4; c += 64) {
                 const float4 p4 = *reinterpret_cast<const float4*>(prow + 4 * c);
                 const float4 q4 = *reinterpret_cast<const float4*>(q + 4 * c);
-                acc += p4.x * q4.x + p4.y * q4.y + p4.z * q4.z + p4.w * q4.w;
+                acc += ((double)p4.x * q4.x + (double)p4.y * q4.y) + ((double)p4.z * q4.z + (double)p4.w * q4.w);
             }
             const int tail = a.n[m] & 3;
-            if (lane < tail) acc += prow[4 * nm4 + lane] * q[4 * nm4 + lane];
-            acc = wave_sum(acc);
+            if (lane < tail) acc += (double)prow[4 * nm4 + lane] * q[4 * nm4 + lane];
+            acc = wave_sum_d(acc);
             if (a.blockdiag) {
-                if (lane == 0) a.R[(long long)(m - 1) * slab + (long long)i * a.ldr + u] = acc;
+                if (lane == 0) a.R[(long long)(m - 1) * slab + (long long)i * a.ldr + u] = (float)acc;
             } else {
                 tot += acc;
             }
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
         if (lane == 0) {
             const float qL = a.Q[a.L][(long long)i * a.ld[a.L] + u];
             if (a.blockdiag) a.R[(long long)(a.L - 1) * slab + (long long)i * a.ldr + u] = qL;
-            else             a.R[(long long)i * a.ldr + u] = qL + tot;
+            else             a.R[(long long)i * a.ldr + u] = (float)((double)qL + tot);
         }
     }
 }
@@ -215,16 +216,17 @@ __global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int c
     const int j = (c << 10) + 4 * threadIdx.x;
     if (j >= a.n[m]) return;
     const float* __restrict__ pcol = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // HBM-bound pass: fp64 accumulators cost no time and keep the n_L-term sums exact to fp32
+    double ax = 0.0, ay = 0.0, az = 0.0, aw = 0.0;
     // rows are padded to a multiple of 4 floats, so a full float4 is always readable
 #pragma unroll 8
     for (int u = 0; u < a.nL; ++u) {
         const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
-        const float w = rbar[u];
-        acc.x += p4.x * w; acc.y += p4.y * w; acc.z += p4.z * w; acc.w += p4.w * w;
+        const double w = (double)rbar[u];
+        ax += p4.x * w; ay += p4.y * w; az += p4.z * w; aw += p4.w * w;
     }
     float* t = a.T[m] + (long long)i * a.ld[m] + j;
-    *reinterpret_cast<float4*>(t) = acc;
+    *reinterpret_cast<float4*>(t) = make_float4((float)ax, (float)ay, (float)az, (float)aw);
 }
 
 // Both passes in one when n_L <= NLMAX and the hidden widths fit one work-group:
