@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="BASELINE configuration 1..5 (default 2)")
     ap.add_argument("--mv-reps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run one plain copy kernel of known size (dense copy of stored block P^1) so that "
+                         "a counter run can be scaled by what the same counter reads for that copy")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -144,6 +147,13 @@ def main():
         mark(6)
         dn.dn_cg(ctx, g, cfg.lam, 0.0, cfg.cg_iters, dn.DN_BLOCKDIAG, d)
         mark(7)
+
+    if args.copy_calib and cfg.L >= 2:
+        dn.dn_jacobian_prep(ctx, dtheta, dX, dS)
+        Pc = torch.empty(cfg.s * cfg.dims[-1] * cfg.dims[1], dtype=torch.float32, device=dev)
+        dn.dn_jacobian_read(ctx, 1, Pc)     # unpad_rows_kernel: reads and writes 4*|S|*n_L*n_1 bytes
+        torch.cuda.synchronize()
+        print(f"copy-calib: unpad_rows_kernel moved {4 * Pc.numel()} bytes each way", file=sys.stderr)
 
     # warm-up, with every kernel class bracketed once to find the dominant product kernel
     work = work_per_launch(cfg, cfg.s)

@@ -33,7 +33,14 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // four floats that are only known to be 4-byte aligned
 typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 
-enum OperandLayout { KC = 0, RC = 1 };
+// KC: stored [rows][K], K contiguous.  RC: stored [K][rows], kept row-contiguous in LDS.
+// RT: stored [K][rows] like RC, but transposed on the way in: a thread loads four k-consecutive
+//     values of one row (each such load is coalesced across the wave, lanes = consecutive rows) and
+//     writes them to LDS as one 128-bit store in the KC arrangement, so the MFMA side is identical to KC.
+enum OperandLayout { KC = 0, RC = 1, RT = 2 };
+
+// source of the virtual column of ones of an RT operand (read with stride 0)
+__device__ const float dn_ones4[4] = {1.f, 1.f, 1.f, 1.f};
 
 enum Epilogue {
     EP_STORE = 0,         // C = acc
@@ -81,8 +88,8 @@ struct TileFetch {
     static_assert(SLOTS % NT == 0, "every thread owns whole fetch slots");
     static constexpr int PER_THREAD = SLOTS / NT;
     // LDS strides: KC rows are BK+4 floats apart, RC k-rows are ROWS+8 floats apart.
-    static constexpr int LDS_STRIDE = (LAYOUT == KC) ? (BK + 4) : (ROWS + 8);
-    static constexpr int LDS_FLOATS = (LAYOUT == KC) ? ROWS * (BK + 4) : BK * (ROWS + 8);
+    static constexpr int LDS_STRIDE = (LAYOUT != RC) ? (BK + 4) : (ROWS + 8);
+    static constexpr int LDS_FLOATS = (LAYOUT != RC) ? ROWS * (BK + 4) : BK * (ROWS + 8);
 
     struct Addr {
         const float* p[PER_THREAD];   // KC: &op[row][4*kq]; RC: &op[0][row]
@@ -90,6 +97,7 @@ struct TileFetch {
         int mode[PER_THREAD];
         int rem[PER_THREAD];          // RC mode 2: valid rows counted from this slot's first row
         int ones_at[PER_THREAD];      // RC mode 2: position (0..3) of the virtual ones row, else -1
+        long long ldp[PER_THREAD];    // RT: element stride between consecutive k of this slot (0 for the ones row)
         long long ld;
     };
 
@@ -99,8 +107,22 @@ struct TileFetch {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int s = tid + i * NT;
-            a.mode[i] = 0; a.p[i] = base; a.q[i] = 0; a.rem[i] = 0; a.ones_at[i] = -1;
-            if (LAYOUT == KC) {
+            a.mode[i] = 0; a.p[i] = base; a.q[i] = 0; a.rem[i] = 0; a.ones_at[i] = -1; a.ldp[i] = ld;
+            if (LAYOUT == RT) {
+                // slot = (row = s % ROWS, four consecutive k starting at 4 * (s / ROWS))
+                const int row = row0 + s % ROWS;
+                a.q[i] = 4 * (s / ROWS);
+                const int real_rows = ones_row >= 0 ? rows_total - 1 : rows_total;  // rows that exist in memory
+                if (row == ones_row) {
+                    a.p[i] = dn_ones4;
+                    a.ldp[i] = 0;
+                    a.mode[i] = 1;
+                } else {
+                    // rows past the end read the last real row; they only feed outputs that are never stored
+                    a.p[i] = base + (row < real_rows ? row : real_rows - 1);
+                    a.mode[i] = row < real_rows ? 1 : 4;
+                }
+            } else if (LAYOUT == KC) {
                 const int row = row0 + s / (BK / 4);
                 a.q[i] = 4 * (s % (BK / 4));
                 // rows past the end read the last valid row
@@ -142,7 +164,10 @@ struct TileFetch {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (LAYOUT == KC) {
+            if (LAYOUT == RT) {
+                const float* p = a.p[i] + (long long)(k0 + a.q[i]) * a.ldp[i];
+                x = make_float4(p[0], p[a.ldp[i]], p[2 * a.ldp[i]], p[3 * a.ldp[i]]);
+            } else if (LAYOUT == KC) {
                 const f32x4u t = *reinterpret_cast<const f32x4u*>(a.p[i] + k0);
                 x = make_float4(t[0], t[1], t[2], t[3]);
             } else {
@@ -158,12 +183,48 @@ struct TileFetch {
         }
     }
 
+    // One slot of a whole tile whose slots are all of mode 1 or 4 (checked once per work-group).
+    __device__ __forceinline__ void load_clean_one(const Addr& a, int k0, int i) {
+        if (LAYOUT == RT) {
+            const float* p = a.p[i] + (long long)(k0 + a.q[i]) * a.ldp[i];
+            v[i] = make_float4(p[0], p[a.ldp[i]], p[2 * a.ldp[i]], p[3 * a.ldp[i]]);
+        } else {
+            const float* p = (LAYOUT == KC) ? a.p[i] + k0 : a.p[i] + (long long)(k0 + a.q[i]) * a.ld;
+            const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
+            v[i] = make_float4(t[0], t[1], t[2], t[3]);
+        }
+    }
+
+    __device__ __forceinline__ void store_one(float* lds, int tid, int i) const {
+        *reinterpret_cast<float4*>(lds + lds_offset(tid + i * NT)) = v[i];
+    }
+
+    __device__ static __forceinline__ int lds_offset(int s) {
+        if (LAYOUT == KC) return (s / (BK / 4)) * LDS_STRIDE + 4 * (s % (BK / 4));
+        if (LAYOUT == RT) return (s % ROWS) * LDS_STRIDE + 4 * (s / ROWS);
+        return (s / (ROWS / 4)) * LDS_STRIDE + 4 * (s % (ROWS / 4));
+    }
+
+    __device__ static __forceinline__ bool all_clean(const Addr& a) {
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) ok = ok && (a.mode[i] == 1 || a.mode[i] == 4);
+        return ok;
+    }
+
     // Last, partial K tile: every element is checked against k_end.
     __device__ __forceinline__ void load_tail(const Addr& a, int k0, int k_end) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (LAYOUT == KC) {
+            if (LAYOUT == RT) {
+                const int k = k0 + a.q[i];
+                const float* p = a.p[i] + (long long)k * a.ldp[i];
+                if (k + 0 < k_end) x.x = p[0];
+                if (k + 1 < k_end) x.y = p[a.ldp[i]];
+                if (k + 2 < k_end) x.z = p[2 * a.ldp[i]];
+                if (k + 3 < k_end) x.w = p[3 * a.ldp[i]];
+            } else if (LAYOUT == KC) {
                 const int k = k0 + a.q[i];
                 const float* p = a.p[i] + k0;
                 if (a.mode[i] == 1) {
@@ -192,20 +253,14 @@ struct TileFetch {
     // (or columns) beyond M (or N), which the epilogue never writes, so they need no zeroing.
     __device__ __forceinline__ void store(const Addr& a, float* lds, int tid) const {
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int s = tid + i * NT;
-            int off;
-            if (LAYOUT == KC) off = (s / (BK / 4)) * LDS_STRIDE + 4 * (s % (BK / 4));
-            else              off = (s / (ROWS / 4)) * LDS_STRIDE + 4 * (s % (ROWS / 4));
-            *reinterpret_cast<float4*>(lds + off) = v[i];
-        }
+        for (int i = 0; i < PER_THREAD; ++i) *reinterpret_cast<float4*>(lds + lds_offset(tid + i * NT)) = v[i];
     }
 };
 
 // Fetch the four k-step values of one 32-row MFMA operand block for k-group kk (8 k values).
 template <int ROWS, int BK, int LAYOUT>
 __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int h, float (&f)[4]) {
-    if (LAYOUT == KC) {
+    if (LAYOUT != RC) {
         float4 x = *reinterpret_cast<const float4*>(lds + row * (BK + 4) + kk * 8 + 4 * h);
         f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
     } else {
@@ -219,14 +274,15 @@ __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int
 
 // BM x BN macro tile, 4 waves arranged WGM x WGN, each wave owning (BM/WGM) x (BN/WGN).
 // PF = number of K tiles kept in flight in registers ahead of the one being multiplied.
-template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int EP, int PF>
+// PIN = use the hand-interleaved steady-state loop.
+template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int EP, int PF, bool PIN>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     constexpr int NT = 256;
     static_assert(WGM * WGN == 4, "four waves per work-group");
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / 32, FN = WN / 32;
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
-    static_assert(PF == 2 || PF == 4, "prefetch depth must be even so LDS buffer parity is static");
+    static_assert(PF % 2 == 0 && PF >= 2 && PF <= 8, "prefetch depth must be even so LDS buffer parity is static");
     using FetchA = TileFetch<BM, BK, LA, NT>;
     using FetchB = TileFetch<BN, BK, LB, NT>;
 
@@ -283,21 +339,34 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
         if (kt < nfull) { fa[slot].load_full(aa, k0); fb[slot].load_full(ab, k0); }
         else            { fa[slot].load_tail(aa, k0, k_end); fb[slot].load_tail(ab, k0, k_end); }
     };
+    // Fragment reads run one k-group ahead of the MFMAs that use them, so the LDS latency of group
+    // kk+1 is covered by the MFMAs of group kk.
     auto multiply = [&](int cur) {
+        constexpr int KG = BK / 8;
+        float af[2][FM][4], bf[2][FN][4];
 #pragma unroll
-        for (int kk = 0; kk < BK / 8; ++kk) {
-            float af[FM][4], bf[FN][4];
+        for (int i = 0; i < FM; ++i) frag_read<BM, BK, LA>(ldsA[cur], wm0 + i * 32 + r, 0, h, af[0][i]);
 #pragma unroll
-            for (int i = 0; i < FM; ++i) frag_read<BM, BK, LA>(ldsA[cur], wm0 + i * 32 + r, kk, h, af[i]);
+        for (int j = 0; j < FN; ++j) frag_read<BN, BK, LB>(ldsB[cur], wn0 + j * 32 + r, 0, h, bf[0][j]);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) frag_read<BN, BK, LB>(ldsB[cur], wn0 + j * 32 + r, kk, h, bf[j]);
+        for (int kk = 0; kk < KG; ++kk) {
+            const int cb = kk & 1;
+            if (kk + 1 < KG) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+                    frag_read<BM, BK, LA>(ldsA[cur], wm0 + i * 32 + r, kk + 1, h, af[cb ^ 1][i]);
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    frag_read<BN, BK, LB>(ldsB[cur], wn0 + j * 32 + r, kk + 1, h, bf[cb ^ 1][j]);
+            }
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][s4], bf[j][s4], acc[i][j], 0, 0, 0);
+                        acc[i][j] =
+                            __builtin_amdgcn_mfma_f32_32x32x2f32(af[cb][i][s4], bf[cb][j][s4], acc[i][j], 0, 0, 0);
         }
     };
 
@@ -334,8 +403,162 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     int since_flush = 0;
 
     int kt0 = 0;
-    // steady state: every refill in this round is a whole tile (kt0 + PF-1 + PF < nfull)
-    for (; kt0 + 2 * PF <= nfull; kt0 += PF) {
+    // ---- steady state -------------------------------------------------------------------------
+    // Entered only by work-groups whose fetch slots are all plain four-wide loads (no ragged rows, no
+    // virtual column in this tile); the others do all their tiles in the checked loop below.
+    // A wave issues in order, so a memory instruction only overlaps the matrix pipe if it sits
+    // between two MFMAs.  Each K-tile is therefore laid out by hand as
+    //     [LDS reads of k-group 0]
+    //     {MFMA of the previous tile's last k-group} x {LDS writes of tile kt+1, global loads of tile kt+PF}
+    //     {MFMA of k-group g} x {LDS reads of k-group g+1, remaining writes/loads}     g = 0..KG-2
+    //     [barrier]
+    // with one memory instruction after each MFMA and scheduling fences that keep the compiler from
+    // regrouping them.  The last k-group of a tile is multiplied after the barrier, which covers the
+    // LDS latency of the next tile's first reads.
+    // Measured: the hand-placed order (PIN) wins when a launch has few work-groups per CU, so that a wave
+    // has little company on its SIMD, and both operands are K-contiguous (few, wide LDS reads); with many
+    // resident waves, or with row-contiguous operands (four narrow LDS reads per fragment), the compiler's
+    // own schedule of the plain loop below is as good or better.  The host picks per launch.
+    constexpr bool kPinned = PIN;
+    const bool clean = __syncthreads_and((FetchA::all_clean(aa) && FetchB::all_clean(ab)) ? 1 : 0) != 0;
+    if (!kPinned) {
+        // plain steady state: whole tiles only, no k checks, compiler-scheduled
+        for (; kt0 + 2 * PF <= nfull; kt0 += PF) {
+            if (since_flush >= kFlushTiles) {
+                since_flush = 0;
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            acc2[i][j][e] += acc[i][j][e];
+                            acc[i][j][e] = 0.f;
+                        }
+            }
+            since_flush += PF;
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                // register slot u held tile kt0+u, which already sits in LDS: refill it with tile kt0+u+PF
+                const int k0 = k_begin + (kt0 + u + PF) * BK;
+                fa[u].load_full(aa, k0);
+                fb[u].load_full(ab, k0);
+                multiply(u & 1);                 // u & 1 == kt & 1 because PF is even
+                fa[(u + 1) % PF].store(aa, ldsA[(u & 1) ^ 1], tid);
+                fb[(u + 1) % PF].store(ab, ldsB[(u & 1) ^ 1], tid);
+                __syncthreads();
+            }
+        }
+    } else if (clean && 2 * PF <= nfull) {
+        constexpr int KG = BK / 8;
+        constexpr int NA = FetchA::PER_THREAD, NB = FetchB::PER_THREAD;
+        constexpr int NOPS = 2 * (NA + NB);
+        float daf[FM][4], dbf[FN][4];          // fragments of the deferred k-group
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) daf[i][c] = 0.f;
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) dbf[j][c] = 0.f;
+
+        for (; kt0 + 2 * PF <= nfull; kt0 += PF) {
+            if (since_flush >= kFlushTiles) {
+                since_flush = 0;
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            acc2[i][j][e] += acc[i][j][e];
+                            acc[i][j][e] = 0.f;
+                        }
+            }
+            since_flush += PF;
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int cur = u & 1;                      // == kt & 1 because PF is even
+                const int k0 = k_begin + (kt0 + u + PF) * BK;
+                const float* la = ldsA[cur];
+                const float* lb = ldsB[cur];
+                // memory instruction number `op` of this tile: stores of slot u+1 first, then refills of slot u
+                auto mem_op = [&](int op) {
+                    if (op < NA)               fa[(u + 1) % PF].store_one(ldsA[cur ^ 1], tid, op);
+                    else if (op < NA + NB)     fb[(u + 1) % PF].store_one(ldsB[cur ^ 1], tid, op - NA);
+                    else if (op < 2 * NA + NB) fa[u].load_clean_one(aa, k0, op - NA - NB);
+                    else if (op < NOPS)        fb[u].load_clean_one(ab, k0, op - 2 * NA - NB);
+                };
+                float af[2][FM][4], bf[2][FN][4];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) frag_read<BM, BK, LA>(la, wm0 + i * 32 + r, 0, h, af[0][i]);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) frag_read<BN, BK, LB>(lb, wn0 + j * 32 + r, 0, h, bf[0][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                int op = 0;
+                // deferred k-group of the previous tile
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(daf[i][s4], dbf[j][s4], acc[i][j], 0, 0, 0);
+                            mem_op(op++);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                // k-groups 0 .. KG-2 of this tile, reading the next group's fragments on the way
+#pragma unroll
+                for (int kk = 0; kk + 1 < KG; ++kk) {
+                    const int cb = kk & 1;
+                    int rd = 0;
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                        for (int i = 0; i < FM; ++i)
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cb][i][s4], bf[cb][j][s4],
+                                                                                 acc[i][j], 0, 0, 0);
+                                if (rd < FM)
+                                    frag_read<BM, BK, LA>(la, wm0 + rd * 32 + r, kk + 1, h, af[cb ^ 1][rd]);
+                                else if (rd < FM + FN)
+                                    frag_read<BN, BK, LB>(lb, wn0 + (rd - FM) * 32 + r, kk + 1, h, bf[cb ^ 1][rd - FM]);
+                                else
+                                    mem_op(op++);
+                                ++rd;
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                }
+                // whatever did not fit between MFMAs
+#pragma unroll
+                for (int rest = 0; rest < NOPS; ++rest)
+                    if (rest >= op) mem_op(rest);
+                // the last k-group waits until after the barrier
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) daf[i][c] = af[(KG - 1) & 1][i][c];
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) dbf[j][c] = bf[(KG - 1) & 1][j][c];
+                __syncthreads();
+            }
+        }
+        // the deferred k-group of the last steady-state tile
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(daf[i][s4], dbf[j][s4], acc[i][j], 0, 0, 0);
+    }
+    // checked loop: the tiles the steady state did not take; refills stop at nk, the last tile may be
+    // ragged, slots may need element-wise loads
+    for (; kt0 < nk; kt0 += PF) {
         if (since_flush >= kFlushTiles) {
             since_flush = 0;
 #pragma unroll
@@ -349,21 +572,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
                     }
         }
         since_flush += PF;
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int kt = kt0 + u;
-            // register slot u held tile kt, which already sits in LDS: refill it with tile kt + PF
-            const int k0 = k_begin + (kt + PF) * BK;
-            fa[u].load_full(aa, k0);
-            fb[u].load_full(ab, k0);
-            multiply(u & 1);                 // u & 1 == kt & 1 because PF is even
-            fa[(u + 1) % PF].store(aa, ldsA[(u & 1) ^ 1], tid);
-            fb[(u + 1) % PF].store(ab, ldsB[(u & 1) ^ 1], tid);
-            __syncthreads();
-        }
-    }
-    // drain: refills stop at nk, the last tile may be ragged
-    for (; kt0 < nk; kt0 += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int kt = kt0 + u;

@@ -20,9 +20,7 @@ using namespace dn;
 namespace {
 
 constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
-// K-tile depth and register prefetch depth of the two macro-tile shapes
-constexpr int kBK64 = 16, kPF64 = 4;
-constexpr int kBK128 = 16, kPF128 = 2;
+// K-tile depths; slices of split sums are cut at multiples of the deepest
 constexpr int kBKmax = 32;
 
 enum KernelClass {
@@ -201,27 +199,37 @@ int group_tiles(const GemmGroup& g, int BM, int BN) {
     return t;
 }
 
-template <int BM, int BN, int BK, int PF, int LA, int LB, int EP>
+template <int BM, int BN, int BK, int PF, int LA, int LB, int EP, bool PIN = false>
 hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     if (g.total_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, EP, PF>), dim3(g.total_tiles), dim3(256), 0, st, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, EP, PF, PIN>), dim3(g.total_tiles), dim3(256), 0, st,
+                       g);
     return hipGetLastError();
 }
 
+// Tile variants (measured on MI355X):
+//   128x128, K-tile 16, 2 tiles in flight             large products of K-contiguous operands (>= 1024 tiles)
+//   64x64,   K-tile 16, 4 in flight, pinned schedule  launches of <= 4 work-groups per CU
+//   64x64,   K-tile 16, 4 in flight                   everything else
 template <int LA, int LB, int EP>
 hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
     if (tile == 128) {
-        finalize_group(g, 128, 128, kBK128, splits);
-        return launch_gemm_t<128, 128, kBK128, kPF128, LA, LB, EP>(g, st);
+        finalize_group(g, 128, 128, 16, splits);
+        return launch_gemm_t<128, 128, 16, 2, LA, LB, EP>(g, st);
     }
-    finalize_group(g, 64, 64, kBK64, splits);
-    return launch_gemm_t<64, 64, kBK64, kPF64, LA, LB, EP>(g, st);
+    finalize_group(g, 64, 64, 16, splits);
+    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, EP, true>(g, st);
+    return launch_gemm_t<64, 64, 16, 4, LA, LB, EP>(g, st);
 }
 
-// Measured on MI355X: 64x64 tiles win on every shape of the path except large products with both
-// operands K-contiguous, where 128x128 tiles are ~6% faster once there are >= 4 of them per CU.
+// Measured on MI355X: 64x64 tiles win on every shape of the path except products with both operands
+// K-contiguous and both output dimensions >= 1024, where 128x128 tiles are ~5% faster once there are
+// >= 4 of them per CU.
 int pick_tile(const GemmGroup& g, bool both_k_contiguous) {
-    return (both_k_contiguous && group_tiles(g, 128, 128) >= 1024) ? 128 : 64;
+    if (!both_k_contiguous || group_tiles(g, 128, 128) < 1024) return 64;
+    for (int i = 0; i < g.nprob; ++i)
+        if (g.p[i].M < 1024 || g.p[i].N < 1024) return 64;
+    return 128;
 }
 
 int pick_splits(int tiles, int K) {
@@ -463,7 +471,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RC, RC, EP_STORE>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, RT, EP_STORE>(g, pl.tile, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
@@ -628,7 +636,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             p.split_stride = (long long)c->dims[m] * c->ldw[m];
             ProfScope ps(c, KC_GEMM_TN_GRAD);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RC, RC, EP_STORE>(g1, plans[m].tile, plans[m].splits, c->stream)));
+            DN_HIP(c, (launch_gemm<RT, RT, EP_STORE>(g1, plans[m].tile, plans[m].splits, c->stream)));
             DN_HIP(c, ps.end());
         }
         if (m > 1) {
@@ -644,7 +652,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             const int tile = pick_tile(g2, false);
             ProfScope ps(c, KC_GEMM_BACK);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g2, tile, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, RT, EP_DSIGMOID>(g2, tile, 1, c->stream)));
             DN_HIP(c, ps.end());
             cur ^= 1;
         }
@@ -690,7 +698,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         const int tile = pick_tile(g, false);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, RC, EP_DSIGMOID>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, RT, EP_DSIGMOID>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     c->s_cur = s;
