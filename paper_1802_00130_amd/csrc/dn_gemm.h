@@ -42,20 +42,20 @@ enum OperandLayout { KC = 0, RC = 1, RT = 2 };
 // source of the virtual column of ones of an RT operand (read with stride 0)
 __device__ const float dn_ones4[4] = {1.f, 1.f, 1.f, 1.f};
 
-enum Epilogue {
-    EP_STORE = 0,         // C = acc
-    EP_BIAS = 1,          // C = acc + bias[n]
-    EP_BIAS_SIGMOID = 2,  // C = 1/(1+exp(-(acc + bias[n])))
-    EP_DSIGMOID = 3       // C = acc * z(1-z), z = aux[(m / auxdiv) * ldaux + n]
-};
+// Epilogue of a problem, applied in this order to every output element (m, n):
+//   x = alpha * acc;  x += bias[n] (if bias);  x = 1/(1+exp(-x)) (if sigmoid);
+//   x *= z(1-z) with z = aux[(m / auxdiv) * ldaux + n] (if aux);  x += add[m * ldadd + n] (if add).
 
 struct GemmProblem {
     const float* A;
     const float* B;
     float* C;
-    const float* bias;   // EP_BIAS*: length N
-    const float* aux;    // EP_DSIGMOID: activations z
-    long long lda, ldb, ldc, ldaux;
+    const float* bias;   // nullable: length N
+    const float* aux;    // nullable: activations z whose sigma' = z(1-z) scales the result
+    const float* add;    // nullable: matrix added last (may be C itself)
+    long long lda, ldb, ldc, ldaux, ldadd;
+    float alpha;         // scale of the accumulated product
+    int sigmoid;         // 1: logistic function after the bias
     long long split_stride;  // elements between the C outputs of consecutive K-slices
     int M, N, K;
     int auxdiv;          // aux row = output row / auxdiv
@@ -275,7 +275,7 @@ __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int
 // BM x BN macro tile, 4 waves arranged WGM x WGN, each wave owning (BM/WGM) x (BN/WGN).
 // PF = number of K tiles kept in flight in registers ahead of the one being multiplied.
 // PIN = use the hand-interleaved steady-state loop.
-template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int EP, int PF, bool PIN>
+template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int PF, bool PIN>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     constexpr int NT = 256;
     static_assert(WGM * WGN == 4, "four waves per work-group");
@@ -589,26 +589,35 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 
     // ---- epilogue: lane holds column n = .. + r and rows 8*(e/4) + 4*h + e%4 of each 32x32 block ----
     float* __restrict__ Cb = P.C + (long long)split * P.split_stride;
+    const bool plain = !P.sigmoid && !P.aux && !P.add;      // uniform: keep the common case branch-free
+    const float alpha = P.alpha;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
         const int n = n0 + wn0 + j * 32 + r;
         if (n >= P.N) continue;
-        float bias = 0.f;
-        if (EP == EP_BIAS || EP == EP_BIAS_SIGMOID) bias = P.bias[n];
+        const float bias = P.bias ? P.bias[n] : 0.f;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
+            if (plain) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-                if (m >= P.M) continue;
-                float x = acc[i][j][e] + acc2[i][j][e];
-                if (EP == EP_BIAS) x += bias;
-                if (EP == EP_BIAS_SIGMOID) x = sigmoidf_fast(x + bias);
-                if (EP == EP_DSIGMOID) {
-                    const float z = P.aux[(long long)(m / P.auxdiv) * P.ldaux + n];
-                    x *= z * (1.0f - z);
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
+                    if (m < P.M) Cb[(long long)m * P.ldc + n] = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
                 }
-                Cb[(long long)m * P.ldc + n] = x;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
+                    if (m >= P.M) continue;
+                    float x = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
+                    if (P.sigmoid) x = sigmoidf_fast(x);
+                    if (P.aux) {
+                        const float z = P.aux[(long long)(m / P.auxdiv) * P.ldaux + n];
+                        x *= z * (1.0f - z);
+                    }
+                    if (P.add) x += P.add[(long long)m * P.ldadd + n];
+                    Cb[(long long)m * P.ldc + n] = x;
+                }
             }
         }
     }

@@ -71,6 +71,16 @@ __global__ __launch_bounds__(256) void jac_init_kernel(const float* __restrict__
     }
 }
 
+// Row copy into a padded layout: dst[r][c] = src[r][c], rows of src are dense.
+__global__ __launch_bounds__(256) void pad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                       long long rows, int cols, long long ld) {
+    const long long total = rows * cols;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const long long rr = e / cols;
+        dst[rr * ld + (e - rr * cols)] = src[e];
+    }
+}
+
 // Dense copy of a stored block (drops the row padding).
 __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                          long long rows, int cols, long long ld) {
@@ -140,6 +150,9 @@ struct StreamArgs {
     float* T[DN_MAX_LAYERS + 1];         // T[m], m = 1..L: [s][ld[m]]
     float* R;                            // [L][s][ldr] (full mode uses slot 0 only)
     long long ldr;
+    // Two-pass kernels only: the block of the last hidden layer is not streamed from memory.  Since
+    // P^{L-1}_i = A^L diag(sigma'(s^{L-1,i})) (Section 3.3 recursion applied once to the identity), its
+    // two products are small dense products with A^L, done by the GEMM engine around these kernels.
     // fused kernel: wave w of a work-group owns float4 columns 64*wcol[w] + lane of layer wlayer[w]
     int nwslots;
     int wlayer[DN_MAX_WSLOTS];
@@ -149,6 +162,9 @@ struct StreamArgs {
 // J v, outer sum of Section 4.2: for sample i and output u,
 //   full:       r_i[u]   = q^{L,i}_u + sum_{m<L} sum_j P^m_i[u][j] q^{m,i}_j
 //   per-layer:  r^m_i[u] =                      sum_j P^m_i[u][j] q^{m,i}_j   (m < L),  r^L_i = q^{L,i}
+// This kernel handles the stored blocks m <= L-2.  The block m = L-1 is applied before it as a small
+// dense product (A^L times sigma'-scaled q^{L-1}), whose result is already inside Q[L] (full) or in
+// slab L-2 of R (per-layer).
 // Work-group = (sample, block of UB outputs); each wave reduces whole rows of P.
 template <int UB>
 __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
@@ -162,7 +178,7 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
         if (u >= a.nL) break;
         // the pass is bound by HBM, so the sums are carried in fp64 at no cost in time
         double tot = 0.0;
-        for (int m = 1; m < a.L; ++m) {
+        for (int m = 1; m + 1 < a.L; ++m) {
             const int nm4 = a.n[m] >> 2;
             const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
             const float* __restrict__ q = a.Q[m] + (long long)i * a.ld[m];
@@ -191,20 +207,21 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
 }
 
 // J^T, inner sum of Section 4.2 with B = 2I:  t^{m,i}_j = sum_u P^m_i[u][j] * 2 r_i[u]  (m < L),
-// t^{L,i} = 2 r_i.  Work-group = (sample, layer, chunk of 1024 columns); threads own 4 columns.
+// t^{L,i} = 2 r_i.  Stored blocks m <= L-2 and the output layer; t^{L-1} is a small dense product
+// done after this kernel.  Work-group = (sample, layer, chunk of 1024 columns); threads own 4 columns.
 __global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int chunks_total) {
     extern __shared__ float rbar[];
     // decode (sample, layer, chunk): chunk list is layer-major within a sample
     const int i = blockIdx.x / chunks_total;
     int c = blockIdx.x - i * chunks_total;
     int m = 1;
-    for (; m < a.L; ++m) {
+    for (; m + 1 < a.L; ++m) {
         const int cm = (a.n[m] + 1023) >> 10;
         if (c < cm) break;
         c -= cm;
     }
     const long long slab = (long long)a.s * a.ldr;
-    if (m == a.L) {
+    if (m + 1 >= a.L) {
         // output layer: identity block
         const float* r = a.R + (a.blockdiag ? (long long)(a.L - 1) * slab : 0) + (long long)i * a.ldr;
         for (int u = threadIdx.x; u < a.nL; u += 256) a.T[a.L][(long long)i * a.ld[a.L] + u] = 2.0f * r[u];
@@ -229,7 +246,9 @@ __global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int c
     *reinterpret_cast<float4*>(t) = make_float4((float)ax, (float)ay, (float)az, (float)aw);
 }
 
-// Both passes in one when n_L <= NLMAX and the hidden widths fit one work-group:
+// Both passes in one when n_L <= NLMAX and the hidden widths fit one work-group (all hidden layers'
+// blocks, including m = L-1, are read from memory here: measured, rebuilding the last one from A^L inside
+// this kernel is slower than streaming it):
 // one work-group per sample, wave w keeps the 4-column strips of P^m_i (all n_L rows) in
 // registers, so every stored element is read from HBM exactly once per product.
 template <int NLMAX>
@@ -254,6 +273,14 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
     for (int u = 0; u < NLMAX; ++u) {
         p[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (live && u < a.nL) p[u] = *reinterpret_cast<const float4*>(pbase + (long long)u * a.ld[m]);
+    }
+    // columns past n_m hold padding: keep them out of the sums
+    if (live) {
+        const int rem = a.n[m] - j;
+        if (rem < 4) {
+#pragma unroll
+            for (int u = 0; u < NLMAX; ++u) { p[u].w = 0.f; if (rem < 3) p[u].z = 0.f; if (rem < 2) p[u].y = 0.f; }
+        }
     }
 #pragma unroll
     for (int u = 0; u < NLMAX; ++u) {

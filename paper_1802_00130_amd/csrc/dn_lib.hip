@@ -33,6 +33,7 @@ enum KernelClass {
     KC_JV_JTV_FUSED,      // product: both passes over P, one read
     KC_JV,                // product: P q
     KC_JTV,               // product: P^T r
+    KC_GEMM_IMPLICIT,     // product: the two small dense products that stand in for block L-1
     KC_TN_REDUCE,         // slice fold + regularisation term
     KC_JAC_INIT,
     KC_GATHER,
@@ -43,7 +44,7 @@ enum KernelClass {
 
 const char* const kClassNames[KC_COUNT] = {
     "gemm_forward", "gemm_backprop", "gemm_tn_grad", "gemm_jacobian_prep", "gemm_q_matvec", "gemm_tn_matvec",
-    "jv_jtv_fused", "jv_rows", "jtv_cols", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
+    "jv_jtv_fused", "jv_rows", "jtv_cols", "gemm_implicit_block", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
 
 inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -79,6 +80,7 @@ struct dn_ctx {
     size_t o_P[DN_MAX_LAYERS + 1] = {0};
     size_t o_Q[DN_MAX_LAYERS + 1] = {0};
     size_t o_T[DN_MAX_LAYERS + 1] = {0};
+    size_t o_AL = 0;
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
     long long tn_floats = 0;
 
@@ -173,6 +175,7 @@ GemmProblem mk_problem(const float* A, long long lda, const float* B, long long 
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.M = M; p.N = N; p.K = K;
     p.auxdiv = 1;
+    p.alpha = 1.0f;
     p.splits = 1;
     p.k_per_split = K;
     return p;
@@ -199,11 +202,10 @@ int group_tiles(const GemmGroup& g, int BM, int BN) {
     return t;
 }
 
-template <int BM, int BN, int BK, int PF, int LA, int LB, int EP, bool PIN = false>
+template <int BM, int BN, int BK, int PF, int LA, int LB, bool PIN = false>
 hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     if (g.total_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, EP, PF, PIN>), dim3(g.total_tiles), dim3(256), 0, st,
-                       g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN>), dim3(g.total_tiles), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
@@ -211,15 +213,15 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
 //   128x128, K-tile 16, 2 tiles in flight             large products of K-contiguous operands (>= 1024 tiles)
 //   64x64,   K-tile 16, 4 in flight, pinned schedule  launches of <= 4 work-groups per CU
 //   64x64,   K-tile 16, 4 in flight                   everything else
-template <int LA, int LB, int EP>
+template <int LA, int LB>
 hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
     if (tile == 128) {
         finalize_group(g, 128, 128, 16, splits);
-        return launch_gemm_t<128, 128, 16, 2, LA, LB, EP>(g, st);
+        return launch_gemm_t<128, 128, 16, 2, LA, LB>(g, st);
     }
     finalize_group(g, 64, 64, 16, splits);
-    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, EP, true>(g, st);
-    return launch_gemm_t<64, 64, 16, 4, LA, LB, EP>(g, st);
+    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, true>(g, st);
+    return launch_gemm_t<64, 64, 16, 4, LA, LB>(g, st);
 }
 
 // Measured on MI355X: 64x64 tiles win on every shape of the path except products with both operands
@@ -278,6 +280,7 @@ void layout_workspace(dn_ctx* c) {
     for (int m = 1; m < L; ++m) c->o_P[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->dims[L] * c->ld[m]);
     for (int m = 1; m <= L; ++m) c->o_Q[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
     for (int m = 1; m <= L; ++m) c->o_T[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
+    c->o_AL = take(cur, sizeof(float) * (size_t)c->dims[L] * c->ld[L >= 2 ? L - 1 : 0]);
     c->o_R = take(cur, sizeof(float) * (size_t)L * c->s_max * c->ldr);
     long long tn = plan_tn(c, c->s_max, true, 0).total;
     for (int m = 1; m <= L; ++m) tn = std::max(tn, plan_tn(c, c->l_max, false, m).total);
@@ -313,8 +316,8 @@ int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0
         const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_FWD);
         DN_HIP(c, ps.err);
-        if (m < c->L) DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS_SIGMOID>(g, tile, 1, c->stream)));
-        else          DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS>(g, tile, 1, c->stream)));
+        g.p[0].sigmoid = m < c->L ? 1 : 0;
+        DN_HIP(c, (launch_gemm<KC, KC>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
         zin = zout;
         ldin = c->ld[m];
@@ -408,7 +411,13 @@ void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
 // out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
 int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
-    // 1. inner sums over t for every layer: Q^m = Z^{m-1} V^m + vb^m
+    StreamArgs a;
+    fill_stream_args(c, a, mode);
+    const bool fused = L >= 2 && nL <= 16 && a.nwslots <= DN_MAX_WSLOTS;
+    const bool bd = mode == DN_BLOCKDIAG;
+    // 1. inner sums over t for every layer: Q^m = Z^{m-1} V^m + vb^m.  On the two-pass path the
+    //    last hidden layer's result is scaled by sigma'(s^{L-1}) on the way out (it is only ever used
+    //    as A^L (sigma' * q^{L-1})).
     {
         GemmGroup g;
         g.nprob = L;
@@ -416,17 +425,19 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             g.p[m - 1] = mk_problem(c->fptr(c->o_ZS[m - 1]), c->ld[m - 1], v + c->woff[m], c->dims[m - 1],
                                     c->fptr(c->o_Q[m]), c->ld[m], s, c->dims[m], c->dims[m - 1]);
             g.p[m - 1].bias = v + c->boff[m];
+            if (!fused && L >= 2 && m == L - 1) {
+                g.p[m - 1].aux = c->fptr(c->o_ZS[L - 1]);
+                g.p[m - 1].ldaux = c->ld[L - 1];
+            }
         }
         const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_Q);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC, EP_BIAS>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
-    // 2. the two passes over the stored blocks
-    StreamArgs a;
-    fill_stream_args(c, a, mode);
-    if (L >= 2 && nL <= 16 && a.nwslots <= DN_MAX_WSLOTS) {
+    // 2. the two passes over the Jacobian blocks
+    if (fused) {
         ProfScope ps(c, KC_JV_JTV_FUSED);
         DN_HIP(c, ps.err);
         const dim3 grid(s), block(64 * a.nwslots);
@@ -437,6 +448,26 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     } else {
+        const long long slab = (long long)s * c->ldr;   // one layer's rows of R
+        if (L >= 2) {
+            // block L-1 applied as a dense product:  (sigma' * q^{L-1}) A^L^T, added to q^L (full) or
+            // kept as r^{L-1} (per-layer)
+            GemmGroup g;
+            g.nprob = 1;
+            GemmProblem& p = g.p[0];
+            float* dst = bd ? c->fptr(c->o_R) + (long long)(L - 2) * slab : c->fptr(c->o_Q[L]);
+            const long long lddst = bd ? c->ldr : c->ld[L];
+            p = mk_problem(c->fptr(c->o_Q[L - 1]), c->ld[L - 1], c->fptr(c->o_AL), c->ld[L - 1], dst, lddst, s, nL,
+                           c->dims[L - 1]);
+            if (!bd) {
+                p.add = dst;
+                p.ldadd = lddst;
+            }
+            ProfScope ps(c, KC_GEMM_IMPLICIT);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, KC>(g, 64, 1, c->stream)));
+            DN_HIP(c, ps.end());
+        }
         {
             ProfScope ps(c, KC_JV);
             DN_HIP(c, ps.err);
@@ -449,10 +480,27 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             ProfScope ps(c, KC_JTV);
             DN_HIP(c, ps.err);
             int chunks = 1;
-            for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 1024);
+            for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
             hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
                                sizeof(float) * nL, c->stream, a, chunks);
             DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+        if (L >= 2) {
+            // t^{L-1} = sigma' * (A^L^T 2r):  T^L already holds 2r (full); per-layer uses 2 r^{L-1}
+            GemmGroup g;
+            g.nprob = 1;
+            GemmProblem& p = g.p[0];
+            const float* src = bd ? c->fptr(c->o_R) + (long long)(L - 2) * slab : c->fptr(c->o_T[L]);
+            const long long ldsrc = bd ? c->ldr : c->ld[L];
+            p = mk_problem(src, ldsrc, c->fptr(c->o_AL), c->ld[L - 1], c->fptr(c->o_T[L - 1]), c->ld[L - 1], s,
+                           c->dims[L - 1], nL);
+            p.aux = c->fptr(c->o_ZS[L - 1]);
+            p.ldaux = c->ld[L - 1];
+            p.alpha = bd ? 2.0f : 1.0f;
+            ProfScope ps(c, KC_GEMM_IMPLICIT);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, RT>(g, 64, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
     }
@@ -471,7 +519,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT, EP_STORE>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, RT>(g, pl.tile, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
@@ -636,7 +684,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             p.split_stride = (long long)c->dims[m] * c->ldw[m];
             ProfScope ps(c, KC_GEMM_TN_GRAD);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RT, RT, EP_STORE>(g1, plans[m].tile, plans[m].splits, c->stream)));
+            DN_HIP(c, (launch_gemm<RT, RT>(g1, plans[m].tile, plans[m].splits, c->stream)));
             DN_HIP(c, ps.end());
         }
         if (m > 1) {
@@ -652,7 +700,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             const int tile = pick_tile(g2, false);
             ProfScope ps(c, KC_GEMM_BACK);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RT, EP_DSIGMOID>(g2, tile, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, RT>(g2, tile, 1, c->stream)));
             DN_HIP(c, ps.end());
             cur ^= 1;
         }
@@ -679,6 +727,10 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
     if (L >= 2) {
         ProfScope ps(c, KC_JAC_INIT);
         DN_HIP(c, ps.err);
+        // keep a copy of A^L: the products rebuild block L-1 from it
+        hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_for((long long)nL * c->dims[L - 1])), dim3(256), 0, c->stream,
+                           theta + c->woff[L], c->fptr(c->o_AL), (long long)nL, c->dims[L - 1], c->ld[L - 1]);
+        DN_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(jac_init_kernel, dim3(grid_for((long long)s * nL * c->dims[L - 1])), dim3(256), 0,
                            c->stream, theta + c->woff[L], c->fptr(c->o_ZS[L - 1]), c->fptr(c->o_P[L - 1]), s, nL,
                            c->dims[L - 1], c->ld[L - 1], c->ld[L - 1]);
@@ -698,7 +750,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         const int tile = pick_tile(g, false);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, RT, EP_DSIGMOID>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, RT>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     c->s_cur = s;

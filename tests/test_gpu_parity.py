@@ -33,6 +33,9 @@ SMALL = {
     # wide enough for 128-tiles and split sums, normal features
     "mid_200-300-260-10": lambda: dn_inputs.custom((200, 300, 260, 10), l=2100, s=700, C=50.0,
                                                    features="normal3", seed=17),
+    # two-pass path (n_L > 16) with one hidden layer (no stored block at all) and with four
+    "twopass_L2_9-14-20": lambda: dn_inputs.custom((9, 14, 20), l=70, s=37, C=1.2, seed=19),
+    "twopass_L5_10-9-8-7-11-24": lambda: dn_inputs.custom((10, 9, 8, 7, 11, 24), l=90, s=41, C=2.5, seed=20),
     # single output (the paper's two-class setting uses n_L = 1)
     "nL1_16-12-1": lambda: dn_inputs.custom((16, 12, 1), l=64, s=30, C=1.0, seed=18),
 }
