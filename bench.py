@@ -52,6 +52,24 @@ def work_per_launch(cfg, s):
     }
 
 
+def measured_traffic(workload, kernel_class):
+    """HBM bytes per launch (fetch + write) of a kernel class from the committed counter summary, or None.
+
+    The summary is written from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this same script and
+    scaled by what the same counters read for a plain copy kernel of known size.
+    """
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == kernel_class:
+                    return float(parts[1]) + float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def matvec_flops(cfg, s):
     d = cfg.dims
     L = len(d) - 1
@@ -200,7 +218,7 @@ def main():
         achieved = unit_work / (avg_ms * 1e-3) / 1e9
         peak, unit = PEAK_HBM_GBS, "GB/s"
     roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None, "avg_kernel_ms": avg_ms, "launches": int(launches),
+                "frac": achieved / peak, "traffic": measured_traffic(cfg.name, dominant), "avg_kernel_ms": avg_ms, "launches": int(launches),
                 "work_per_launch": unit_work}
 
     mv_tflops = matvec_flops(cfg, cfg.s) / (mv_ms * 1e-3) / 1e12

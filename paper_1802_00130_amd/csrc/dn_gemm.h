@@ -275,7 +275,9 @@ __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int
 // BM x BN macro tile, 4 waves arranged WGM x WGN, each wave owning (BM/WGM) x (BN/WGN).
 // PF = number of K tiles kept in flight in registers ahead of the one being multiplied.
 // PIN = use the hand-interleaved steady-state loop.
-template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int PF, bool PIN>
+// CLS = caller's kernel-class number; it changes no code, only the symbol, so that a profiler's
+//       per-kernel statistics separate the call sites (forward, back-propagation, sweeps, products...).
+template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int PF, bool PIN, int CLS>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     constexpr int NT = 256;
     static_assert(WGM * WGN == 4, "four waves per work-group");

@@ -140,7 +140,8 @@ hipError_t prof_event(dn_ctx* c, hipEvent_t* ev) {
         c->free_events.pop_back();
         return hipSuccess;
     }
-    return hipEventCreate(ev);
+    // no system-scope fence at the record: the bracket should perturb the stream as little as possible
+    return hipEventCreateWithFlags(ev, hipEventDisableSystemFence);
 }
 
 struct ProfScope {
@@ -202,10 +203,11 @@ int group_tiles(const GemmGroup& g, int BM, int BN) {
     return t;
 }
 
-template <int BM, int BN, int BK, int PF, int LA, int LB, bool PIN = false>
+template <int BM, int BN, int BK, int PF, int LA, int LB, int CLS, bool PIN = false>
 hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     if (g.total_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN>), dim3(g.total_tiles), dim3(256), 0, st, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN, CLS>), dim3(g.total_tiles), dim3(256), 0, st,
+                       g);
     return hipGetLastError();
 }
 
@@ -213,15 +215,15 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
 //   128x128, K-tile 16, 2 tiles in flight             large products of K-contiguous operands (>= 1024 tiles)
 //   64x64,   K-tile 16, 4 in flight, pinned schedule  launches of <= 4 work-groups per CU
 //   64x64,   K-tile 16, 4 in flight                   everything else
-template <int LA, int LB>
+template <int LA, int LB, int CLS>
 hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
     if (tile == 128) {
         finalize_group(g, 128, 128, 16, splits);
-        return launch_gemm_t<128, 128, 16, 2, LA, LB>(g, st);
+        return launch_gemm_t<128, 128, 16, 2, LA, LB, CLS>(g, st);
     }
     finalize_group(g, 64, 64, 16, splits);
-    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, true>(g, st);
-    return launch_gemm_t<64, 64, 16, 4, LA, LB>(g, st);
+    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
+    return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS>(g, st);
 }
 
 // Measured on MI355X: 64x64 tiles win on every shape of the path except products with both operands
@@ -317,7 +319,7 @@ int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0
         ProfScope ps(c, KC_GEMM_FWD);
         DN_HIP(c, ps.err);
         g.p[0].sigmoid = m < c->L ? 1 : 0;
-        DN_HIP(c, (launch_gemm<KC, KC>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_FWD>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
         zin = zout;
         ldin = c->ld[m];
@@ -433,7 +435,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_Q);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 2. the two passes over the Jacobian blocks
@@ -465,7 +467,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             }
             ProfScope ps(c, KC_GEMM_IMPLICIT);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, KC>(g, 64, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
         {
@@ -500,7 +502,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             p.alpha = bd ? 2.0f : 1.0f;
             ProfScope ps(c, KC_GEMM_IMPLICIT);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RT>(g, 64, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
     }
@@ -519,7 +521,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
@@ -684,7 +686,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             p.split_stride = (long long)c->dims[m] * c->ldw[m];
             ProfScope ps(c, KC_GEMM_TN_GRAD);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RT, RT>(g1, plans[m].tile, plans[m].splits, c->stream)));
+            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_GRAD>(g1, plans[m].tile, plans[m].splits, c->stream)));
             DN_HIP(c, ps.end());
         }
         if (m > 1) {
@@ -700,7 +702,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             const int tile = pick_tile(g2, false);
             ProfScope ps(c, KC_GEMM_BACK);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RT>(g2, tile, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
             DN_HIP(c, ps.end());
             cur ^= 1;
         }
@@ -750,7 +752,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         const int tile = pick_tile(g, false);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, RT>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_PREP>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     c->s_cur = s;
