@@ -81,6 +81,27 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const float* __restrict__
     }
 }
 
+// dst[c][r] = src[r][c] for a dense rows x cols matrix (32x32 tiles through LDS).  Used to keep
+// W^m (the transpose of the theta slice A^m) beside A^m, so that products with A^m as the right
+// operand also read both operands K-contiguously.
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                        int rows, int cols) {
+    __shared__ float tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) {
+        const int rr = by + ty + k, cc = bx + tx;
+        if (rr < rows && cc < cols) tile[ty + k][tx] = src[(long long)rr * cols + cc];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) {
+        const int cc = bx + ty + k, rr = by + tx;
+        if (rr < rows && cc < cols) dst[(long long)cc * rows + rr] = tile[tx][ty + k];
+    }
+}
+
 // Dense copy of a stored block (drops the row padding).
 __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                          long long rows, int cols, long long ld) {

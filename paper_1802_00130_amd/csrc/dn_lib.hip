@@ -81,6 +81,7 @@ struct dn_ctx {
     size_t o_Q[DN_MAX_LAYERS + 1] = {0};
     size_t o_T[DN_MAX_LAYERS + 1] = {0};
     size_t o_AL = 0;
+    size_t o_WT = 0;           // W^m = (A^m)^T for m = 2..L, dense, at the theta offsets of A^m
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
     long long tn_floats = 0;
 
@@ -283,6 +284,7 @@ void layout_workspace(dn_ctx* c) {
     for (int m = 1; m <= L; ++m) c->o_Q[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
     for (int m = 1; m <= L; ++m) c->o_T[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
     c->o_AL = take(cur, sizeof(float) * (size_t)c->dims[L] * c->ld[L >= 2 ? L - 1 : 0]);
+    c->o_WT = take(cur, sizeof(float) * (size_t)round_up(c->n, 64));
     c->o_R = take(cur, sizeof(float) * (size_t)L * c->s_max * c->ldr);
     long long tn = plan_tn(c, c->s_max, true, 0).total;
     for (int m = 1; m <= L; ++m) tn = std::max(tn, plan_tn(c, c->l_max, false, m).total);
@@ -298,7 +300,20 @@ void layout_workspace(dn_ctx* c) {
     c->ws_bytes = cur;
 }
 
-int grid_for(long long total, int per_block = 256 * 8) {
+int grid_for(long long total, int per_block = 256 * 8);
+
+// W^m = (A^m)^T for layers m_lo..m_hi into the workspace
+int transpose_weights(dn_ctx* c, const float* theta, int m_lo, int m_hi) {
+    for (int m = m_lo; m <= m_hi; ++m) {
+        const int rows = c->dims[m], cols = c->dims[m - 1];
+        hipLaunchKernelGGL(transpose_kernel, dim3(cdiv(cols, 32), cdiv(rows, 32)), dim3(256), 0, c->stream,
+                           theta + c->woff[m], c->fptr(c->o_WT) + c->woff[m], rows, cols);
+        DN_HIP(c, hipGetLastError());
+    }
+    return DN_OK;
+}
+
+int grid_for(long long total, int per_block) {
     long long b = (total + per_block - 1) / per_block;
     return (int)std::max<long long>(1, std::min<long long>(b, 256 * 16));
 }
@@ -651,6 +666,10 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
     int cur = 0;
     rc = objective(c, theta, Y, l, c->fptr(c->o_D[cur]), c->ld[L], nullptr, f_host);
     if (rc != DN_OK) return rc;
+    if (L >= 2) {
+        rc = transpose_weights(c, theta, 2, L);
+        if (rc != DN_OK) return rc;
+    }
     TnPlan plans[DN_MAX_LAYERS + 1];
     // partial buffers of different layers must not overlap: give each layer its own range
     long long tn_off = 0;
@@ -694,15 +713,15 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
             GemmGroup g2;
             g2.nprob = 1;
             GemmProblem& p = g2.p[0];
-            p = mk_problem(delta, c->ld[m], theta + c->woff[m], c->dims[m - 1], c->fptr(c->o_D[cur ^ 1]),
+            p = mk_problem(delta, c->ld[m], c->fptr(c->o_WT) + c->woff[m], c->dims[m], c->fptr(c->o_D[cur ^ 1]),
                            c->ld[m - 1], l, c->dims[m - 1], c->dims[m]);
             p.aux = zprev;
             p.ldaux = ldprev;
             p.auxdiv = 1;
-            const int tile = pick_tile(g2, false);
+            const int tile = pick_tile(g2, true);
             ProfScope ps(c, KC_GEMM_BACK);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
             DN_HIP(c, ps.end());
             cur ^= 1;
         }
@@ -739,20 +758,24 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     }
+    if (L >= 3) {
+        rc = transpose_weights(c, theta, 2, L - 1);
+        if (rc != DN_OK) return rc;
+    }
     // P^{m-1} = (P^m (W^m)^T) * sigma'(s^{m-1}):  the n_L backward sweeps of all samples as one product
     for (int m = L - 1; m >= 2; --m) {
         GemmGroup g;
         g.nprob = 1;
         GemmProblem& p = g.p[0];
-        p = mk_problem(c->fptr(c->o_P[m]), c->ld[m], theta + c->woff[m], c->dims[m - 1], c->fptr(c->o_P[m - 1]),
+        p = mk_problem(c->fptr(c->o_P[m]), c->ld[m], c->fptr(c->o_WT) + c->woff[m], c->dims[m], c->fptr(c->o_P[m - 1]),
                        c->ld[m - 1], s * nL, c->dims[m - 1], c->dims[m]);
         p.aux = c->fptr(c->o_ZS[m - 1]);
         p.ldaux = c->ld[m - 1];
         p.auxdiv = nL;
-        const int tile = pick_tile(g, false);
+        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_PREP>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_PREP>(g, tile, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     c->s_cur = s;
