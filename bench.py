@@ -42,12 +42,14 @@ def work_per_launch(cfg, s):
     wsum = sum(d[m - 1] * d[m] for m in range(1, L + 1))
     hid = sum(d[m] for m in range(1, L))
     pbytes = 4.0 * s * d[L] * hid
+    # the two-pass kernels stream the blocks of layers 1..L-2 only (block L-1 is applied as a dense product)
+    pbytes_streamed = 4.0 * s * d[L] * sum(d[m] for m in range(1, L - 1))
     return {
         "gemm_q_matvec": ("mfma", 2.0 * s * wsum),
         "gemm_tn_matvec": ("mfma", 2.0 * s * wsum),
         "jv_jtv_fused": ("hbm", pbytes),
-        "jv_rows": ("hbm", pbytes),
-        "jtv_cols": ("hbm", pbytes),
+        "jv_rows": ("hbm", pbytes_streamed),
+        "jtv_cols": ("hbm", pbytes_streamed),
         "tn_reduce": ("hbm", 4.0 * 3 * cfg.n_params),
     }
 
