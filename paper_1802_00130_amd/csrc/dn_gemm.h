@@ -62,16 +62,32 @@ struct GemmProblem {
     int tiles_m, tiles_n;
     int splits;          // number of K-slices (>= 1)
     int k_per_split;     // multiple of the K tile
-    int tile_begin;      // first flat tile id of this problem
+    int tile_begin;      // first tile id of this problem within one K-slice of the group
     int b_ones_col;      // 1: column N-1 of op(B) is a virtual column of ones (not read from memory);
                          //    only for a row-contiguous B
 };
 
 struct GemmGroup {
     int nprob;
-    int total_tiles;
+    int total_tiles;      // tiles_per_split * splits
+    int grid;             // work-groups to launch (>= total_tiles)
+    int tiles_per_split;  // output tiles of all problems together
+    int group_m;          // tile rows per super-row of the tile walk (>= 1)
+    int xcd_mode;         // how blockIdx maps to the tile walk, see XcdMode
     GemmProblem p[DN_MAX_GROUP];
 };
+
+// The chip has 8 XCDs, each with its own L2; the dispatcher deals work-groups to them round-robin
+// (work-group b runs on XCD b % 8; checked on MI355X by reading XCC_ID).  Tiles that share an operand
+// panel should therefore not sit at consecutive blockIdx but at blockIdx that are equal modulo 8.
+constexpr int kXcds = 8;
+// XCD_NONE:    blockIdx is the position in the tile walk.
+// XCD_RANGES:  XCD x takes the x-th eighth of the whole walk (launches cut into K-slices: an XCD then
+//              reads one slice of the samples, once).
+// XCD_PER_PROBLEM: XCD x takes the x-th eighth of every problem's tiles, longest problem first (launches
+//              of several problems with different K stay balanced across XCDs).  The grid is padded to
+//              8 * (largest per-XCD count); surplus work-groups exit at once.  One K-slice only.
+enum XcdMode { XCD_NONE = 0, XCD_RANGES = 1, XCD_PER_PROBLEM = 2 };
 
 __device__ __forceinline__ float sigmoidf_fast(float s) { return 1.0f / (1.0f + __expf(-s)); }
 
@@ -292,19 +308,49 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     __shared__ __attribute__((aligned(16))) float ldsB[2][FetchB::LDS_FLOATS];
 
     // ---- which problem / tile / K-slice ----
-    const int bid = blockIdx.x;
-    int pi = 0;
+    // Tile walk (logical ids): K-slice outermost, then problem, then super-rows of group_m tile rows,
+    // inside a super-row down the rows first.  A contiguous stretch of the walk is a compact patch of
+    // the output (its tiles share A and B panels) inside one K-slice (its tiles read the same rows of
+    // both operands of a sum over samples).  XCD x takes the x-th eighth of the walk, so that sharing
+    // happens inside one L2.
+    int lid = blockIdx.x;
+    int split = 0, t = 0, pi = 0;
+    if (g.xcd_mode == XCD_PER_PROBLEM) {
+        const int x = lid % kXcds;
+        int kx = lid / kXcds;
+        pi = -1;
 #pragma unroll
-    for (int i = 1; i < DN_MAX_GROUP; ++i)
-        if (i < g.nprob && bid >= g.p[i].tile_begin) pi = i;
+        for (int i = 0; i < DN_MAX_GROUP; ++i) {
+            if (i < g.nprob && pi < 0) {
+                const int tiles = g.p[i].tiles_m * g.p[i].tiles_n;
+                const int per = tiles / kXcds, rem = tiles % kXcds;
+                const int mine = per + (x < rem ? 1 : 0);
+                if (kx < mine) { pi = i; t = x * per + min(x, rem) + kx; }
+                else kx -= mine;
+            }
+        }
+        if (pi < 0) return;      // padding work-group
+    } else {
+        if (g.xcd_mode == XCD_RANGES) {
+            const int x = lid % kXcds, kx = lid / kXcds;
+            const int per = g.total_tiles / kXcds, rem = g.total_tiles % kXcds;
+            lid = x * per + min(x, rem) + kx;
+        }
+        split = lid / g.tiles_per_split;
+        t = lid - split * g.tiles_per_split;
+#pragma unroll
+        for (int i = 1; i < DN_MAX_GROUP; ++i)
+            if (i < g.nprob && t >= g.p[i].tile_begin) pi = i;
+        t -= g.p[pi].tile_begin;
+    }
     const GemmProblem& P = g.p[pi];
-    int t = bid - P.tile_begin;
-    const int tiles_mn = P.tiles_m * P.tiles_n;
-    const int split = t / tiles_mn;
-    t -= split * tiles_mn;
-    // consecutive tile ids walk down M first so neighbouring work-groups share the B panel
-    const int tm = t % P.tiles_m;
-    const int tn = t / P.tiles_m;
+    const int per_group = g.group_m * P.tiles_n;
+    const int grp = t / per_group;
+    const int first_tm = grp * g.group_m;
+    const int gsz = min(P.tiles_m - first_tm, g.group_m);
+    const int tg = t - grp * per_group;
+    const int tm = first_tm + tg % gsz;
+    const int tn = tg / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
     const int k_begin = split * P.k_per_split;
     const int k_end = min(P.K, k_begin + P.k_per_split);

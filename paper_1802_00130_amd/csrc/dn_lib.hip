@@ -22,6 +22,8 @@ namespace {
 constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
 // K-tile depths; slices of split sums are cut at multiples of the deepest
 constexpr int kBKmax = 32;
+// tile rows per super-row of the tile walk: 8 x 8 tiles are about what one XCD (32 CUs) holds at a time
+constexpr int kGroupM = 8;
 
 enum KernelClass {
     KC_GEMM_FWD = 0,      // forward layer products (all samples or subsample)
@@ -183,7 +185,7 @@ GemmProblem mk_problem(const float* A, long long lda, const float* B, long long 
     return p;
 }
 
-// Fill tile counts / flat tile ranges.  splits applies to every problem of the group.
+// Fill tile counts and the tile walk.  splits applies to every problem of the group.
 void finalize_group(GemmGroup& g, int BM, int BN, int BK, int splits) {
     int begin = 0;
     for (int i = 0; i < g.nprob; ++i) {
@@ -193,9 +195,27 @@ void finalize_group(GemmGroup& g, int BM, int BN, int BK, int splits) {
         p.splits = splits;
         p.k_per_split = (int)round_up(cdiv(p.K, splits), BK);
         p.tile_begin = begin;
-        begin += p.tiles_m * p.tiles_n * splits;
+        begin += p.tiles_m * p.tiles_n;
     }
-    g.total_tiles = begin;
+    g.tiles_per_split = begin;
+    g.total_tiles = begin * splits;
+    g.group_m = kGroupM;
+    g.grid = g.total_tiles;
+    if (splits > 1 || g.nprob == 1) {
+        g.xcd_mode = XCD_RANGES;
+    } else {
+        g.xcd_mode = XCD_PER_PROBLEM;
+        int most = 0;
+        for (int x = 0; x < kXcds; ++x) {
+            int mine = 0;
+            for (int i = 0; i < g.nprob; ++i) {
+                const int tiles = g.p[i].tiles_m * g.p[i].tiles_n;
+                mine += tiles / kXcds + (x < tiles % kXcds ? 1 : 0);
+            }
+            most = std::max(most, mine);
+        }
+        g.grid = kXcds * most;
+    }
 }
 
 int group_tiles(const GemmGroup& g, int BM, int BN) {
@@ -207,8 +227,7 @@ int group_tiles(const GemmGroup& g, int BM, int BN) {
 template <int BM, int BN, int BK, int PF, int LA, int LB, int CLS, bool PIN = false>
 hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     if (g.total_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN, CLS>), dim3(g.total_tiles), dim3(256), 0, st,
-                       g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN, CLS>), dim3(g.grid), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
