@@ -22,6 +22,8 @@ What is computed, and from where in the paper:
 * the stored blocks P^m_i = d z^{L,i} / d s^{m,i} by the backward recursion
                                                 Section 3.3 (recursion for dz^L/dz^{m-1},
                                                 product form of the Jacobian element)
+* one outer Newton iteration: combination with the previous direction, backtracking line
+  search, Levenberg-Marquardt update of lambda  Section 4.3 (two-variable problem), Section 4.5
 
 The G v products here never build P: they differentiate the network directly,
 so they are independent of the factored method the HIP path implements.
@@ -30,7 +32,10 @@ Pins (tests/test_oracle_pins.py): finite differences of f and of the network
 outputs, brute-force dense G from an explicitly assembled Jacobian, symmetry,
 positive definiteness, the gradient-through-Jacobian identity of Section 3.4,
 the no-hidden-layer case against a normal-equations ridge solve, CG against a
-dense solve and its first-step closed form.  No function here is unpinned.
+dense solve and its first-step closed form; the outer iteration against a grid search of
+the two-variable problem, an exhaustive scan of the step sizes, the rule table, and the
+ridge problem where one undamped full step is exact (alpha = 1, rho = 1).
+No function here is unpinned.
 
 theta layout (Section 2.1): for m = 1..L, the n_m x n_{m-1} matrix A^m = (W^m)^T
 stored row-major, then b^m.
@@ -271,3 +276,95 @@ def jacobian_blocks(theta, dims, XS):
             A, _ = layers[m - 1]                                # A[j, t] = w^m_{tj}
             dz = P[m] @ A                                       # [s, nL, n_{m-1}]
     return P[1:]
+
+
+# --------------------------------------------------------------------------- outer Newton iteration
+
+def combine_directions(theta, dims, C, XS, g, d, d_bar, eps=1e-5):
+    """Coefficients (beta1, beta2) of the direction beta1 d + beta2 d_bar  (Section 4.3).
+
+    They minimise  1/2 u^T G^S u + g^T u  over u = beta1 d + beta2 d_bar, G^S being the WHOLE
+    subsampled Gauss-Newton matrix (also when d came from the block-diagonal systems), i.e.
+    they solve the 2x2 system  [[d'Gd, db'Gd], [db'Gd, db'Gdb]] beta = [-g'd, -g'db].
+    If its determinant is <= eps the system is taken as ill-conditioned and (1, 0) is returned.
+    Also returns the three entries (d'Gd, db'Gd, db'Gdb) of the matrix.
+    """
+    g = np.asarray(g, dtype=np.float64)
+    d = np.asarray(d, dtype=np.float64)
+    d_bar = np.asarray(d_bar, dtype=np.float64)
+    Gd = gn_matvec(theta, dims, C, XS, d)
+    Gdb = gn_matvec(theta, dims, C, XS, d_bar)
+    a11, a12, a22 = float(d @ Gd), float(d_bar @ Gd), float(d_bar @ Gdb)
+    b1, b2 = -float(g @ d), -float(g @ d_bar)
+    det = a11 * a22 - a12 * a12
+    if det <= eps:
+        return 1.0, 0.0, (a11, a12, a22)
+    beta1 = (b1 * a22 - b2 * a12) / det
+    beta2 = (a11 * b2 - a12 * b1) / det
+    return beta1, beta2, (a11, a12, a22)
+
+
+def line_search(theta, dims, C, X, Y, f0, gTd, d, eta=1e-4, max_trials=30):
+    """Backtracking line search of Section 4.5: the largest alpha in {1, 1/2, 1/4, ...} with
+    f(theta + alpha d) <= f(theta) + eta alpha grad f(theta)^T d.
+
+    Returns (alpha, f(theta + alpha d), number of f evaluations); alpha = 0 (and f0) if none of the
+    first max_trials candidates is accepted.
+    """
+    theta = np.asarray(theta, dtype=np.float64)
+    d = np.asarray(d, dtype=np.float64)
+    alpha = 1.0
+    for k in range(max_trials):
+        f_new = loss(theta + alpha * d, dims, C, X, Y)
+        if f_new <= f0 + eta * alpha * gTd:
+            return alpha, f_new, k + 1
+        alpha *= 0.5
+    return 0.0, f0, max_trials
+
+
+def lm_update(lam, rho, drop=2.0 / 3.0, boost=1.5):
+    """Levenberg-Marquardt rule of Section 4.5: lambda * drop if rho > 0.75, unchanged if
+    0.25 <= rho <= 0.75, lambda * boost otherwise."""
+    if rho > 0.75:
+        return lam * drop
+    if rho >= 0.25:
+        return lam
+    return lam * boost
+
+
+def newton_step(theta, dims, C, X, Y, S, d_prev, lam, cg_max, sigma=1e-3, eta=1e-4, eps=1e-5,
+                drop=2.0 / 3.0, boost=1.5, blockdiag=False, combine=True, max_trials=30):
+    """One iteration of the subsampled Newton method (Section 4.5, the algorithm summarising the
+    procedure, for a single partition owning every variable):
+
+    gradient on all samples and the Gauss-Newton matrix on the rows S; CG on
+    (G^S + lam I) d = -g (whole matrix, or the per-layer diagonal blocks); optional combination with the
+    previous direction d_prev through the whole G^S; backtracking line search on f; ratio rho of actual to
+    predicted reduction with the undamped G^S; next lam.
+
+    Returns a dict: theta (new iterate), d (direction taken, to be passed as d_prev next time), lam (next),
+    f_old, f_new, alpha, beta (pair), rho, gTd, dGd, cg_iters, f_evals.
+    """
+    theta = np.asarray(theta, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    XS = X[np.asarray(S)]
+    g, f0 = grad(theta, dims, C, X, Y)
+    d, iters, _ = cg(theta, dims, C, XS, g, lam, cg_max, sigma=sigma, blockdiag=blockdiag)
+    if combine:
+        beta1, beta2, (a11, a12, a22) = combine_directions(theta, dims, C, XS, g, d, d_prev, eps)
+        d = beta1 * d + beta2 * np.asarray(d_prev, dtype=np.float64)
+        dGd = beta1 * beta1 * a11 + 2.0 * beta1 * beta2 * a12 + beta2 * beta2 * a22
+    else:
+        beta1, beta2 = 1.0, 0.0
+        dGd = float(d @ gn_matvec(theta, dims, C, XS, d))
+    gTd = float(g @ d)
+    alpha, f_new, evals = line_search(theta, dims, C, X, Y, f0, gTd, d, eta, max_trials)
+    if alpha > 0.0:
+        rho = (f_new - f0) / (alpha * gTd + 0.5 * alpha * alpha * dGd)
+        lam_next = lm_update(lam, rho, drop, boost)
+    else:
+        rho = 0.0
+        lam_next = lam * boost
+    return dict(theta=theta + alpha * d, d=d, lam=lam_next, f_old=f0, f_new=f_new, alpha=alpha,
+                beta=(beta1, beta2), rho=rho, gTd=gTd, dGd=dGd, cg_iters=iters, f_evals=evals)

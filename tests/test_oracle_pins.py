@@ -329,6 +329,120 @@ def test_cg_blockdiag_blocks_stop_independently():
         np.testing.assert_allclose(d[b], dk[b], rtol=1e-12, atol=1e-15)
 
 
+# ------------------------------------------------------------------ outer Newton iteration
+
+def test_direction_combination_minimises_the_two_variable_model():
+    # catches: lambda leaking into the matrix, swapped right-hand sides, the block-diagonal matrix used
+    # instead of the whole one, wrong sign of the right-hand side
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims, l=12, s=8)
+    XS = X[S]
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    rng = np.random.default_rng(5)
+    d = -g + 0.1 * rng.standard_normal(g.size)
+    d_bar = rng.standard_normal(g.size)
+    b1, b2, (a11, a12, a22) = orc.combine_directions(theta, dims, cfg.C, XS, g, d, d_bar, eps=1e-12)
+    G = tiny_ref.dense_gauss_newton(theta, dims, cfg.C, XS)
+    np.testing.assert_allclose([a11, a12, a22], [d @ G @ d, d_bar @ G @ d, d_bar @ G @ d_bar], rtol=1e-6)
+
+    def model(x, y):
+        u = x * d + y * d_bar
+        return 0.5 * u @ G @ u + g @ u
+    best = model(b1, b2)
+    for dx in (-1e-2, 0.0, 1e-2):
+        for dy in (-1e-2, 0.0, 1e-2):
+            assert model(b1 + dx, b2 + dy) >= best - 1e-12
+    # least squares over the span of {d, d_bar} gives the same coefficients
+    D = np.stack([d, d_bar], axis=1)
+    coef = np.linalg.solve(D.T @ G @ D, -D.T @ g)
+    np.testing.assert_allclose([b1, b2], coef, rtol=1e-5)
+    # a zero previous direction (first iteration) or a parallel one is ill-conditioned: keep d
+    assert orc.combine_directions(theta, dims, cfg.C, XS, g, d, np.zeros_like(d))[:2] == (1.0, 0.0)
+    assert orc.combine_directions(theta, dims, cfg.C, XS, g, d, 2.0 * d, eps=1e-9)[:2] == (1.0, 0.0)
+
+
+def test_line_search_returns_the_largest_admissible_power_of_one_half():
+    # catches: accepting the first alpha, a missing eta term, halving before the first trial
+    dims = (4, 3, 3, 2)
+    cfg, X, Y, theta, S = _tiny(dims, l=12, s=8)
+    g, f0 = orc.grad(theta, dims, cfg.C, X, Y)
+    eta = 1e-2
+    for scale in (0.5, 20.0, 150.0):             # the largest scales overshoot and force several halvings
+        d = -scale * g
+        gTd = float(g @ d)
+        alpha, f_new, evals = orc.line_search(theta, dims, cfg.C, X, Y, f0, gTd, d, eta=eta)
+        ok = [tiny_ref.objective(theta + 0.5 ** k * d, dims, cfg.C, X, Y) <= f0 + eta * 0.5 ** k * gTd
+              for k in range(30)]
+        first = ok.index(True)
+        assert alpha == 0.5 ** first and evals == first + 1
+        assert abs(f_new - tiny_ref.objective(theta + alpha * d, dims, cfg.C, X, Y)) <= 1e-12 * abs(f_new)
+    assert first >= 2                            # the scan really had rejections to get past
+    # an ascent direction is never accepted
+    alpha, f_new, evals = orc.line_search(theta, dims, cfg.C, X, Y, f0, float(g @ g), g, eta=eta, max_trials=8)
+    assert alpha == 0.0 and f_new == f0 and evals == 8
+
+
+def test_levenberg_marquardt_rule_table():
+    assert orc.lm_update(3.0, 0.76, drop=0.5, boost=4.0) == 1.5
+    assert orc.lm_update(3.0, 0.75, drop=0.5, boost=4.0) == 3.0
+    assert orc.lm_update(3.0, 0.25, drop=0.5, boost=4.0) == 3.0
+    assert orc.lm_update(3.0, 0.2499, drop=0.5, boost=4.0) == 12.0
+    assert orc.lm_update(3.0, -2.0, drop=0.5, boost=4.0) == 12.0
+    assert orc.lm_update(1.0, 0.9) == pytest.approx(2.0 / 3.0) and orc.lm_update(1.0, 0.1) == 1.5
+
+
+def test_newton_step_is_exact_on_the_ridge_problem():
+    # no hidden layer: f is quadratic and G is its Hessian, so one undamped step over all samples lands on
+    # the minimiser, the full step is accepted, and actual reduction = predicted reduction (rho = 1)
+    dims = (5, 3)
+    cfg, X, Y, theta, _ = _tiny(dims, l=40, s=40, C=2.0)
+    S = np.arange(40)
+    n = theta.size
+    out = orc.newton_step(theta, dims, cfg.C, X, Y, S, np.zeros(n), lam=0.0, cg_max=200, sigma=1e-14,
+                          eta=1e-4, drop=0.5, boost=4.0)
+    Xa = np.hstack([X, np.ones((40, 1))])
+    Wopt = np.linalg.solve(np.eye(6) / cfg.C + 2.0 / 40 * Xa.T @ Xa, 2.0 / 40 * Xa.T @ Y)     # [6 x 3]
+    theta_opt = np.concatenate([Wopt[:5].T.ravel(), Wopt[5]])
+    np.testing.assert_allclose(out["theta"], theta_opt, rtol=1e-8, atol=1e-10)
+    assert out["alpha"] == 1.0 and out["f_evals"] == 1 and out["beta"] == (1.0, 0.0)
+    assert abs(out["rho"] - 1.0) <= 1e-9
+    assert out["lam"] == 0.0
+    assert abs(out["f_new"] - tiny_ref.objective(theta_opt, dims, cfg.C, X, Y)) <= 1e-12
+    # predicted reduction pieces: g'd = -d'Gd at the exact Newton direction
+    assert abs(out["gTd"] + out["dGd"]) <= 1e-9 * abs(out["dGd"])
+
+
+@pytest.mark.parametrize("blockdiag", [False, True])
+def test_newton_iterations_decrease_f_and_follow_the_rules(blockdiag):
+    # catches: theta not advanced, d_prev not carried, lambda updated from the wrong ratio
+    dims = (6, 5, 4, 3)
+    cfg, X, Y, theta, _ = _tiny(dims, l=60, s=20, C=5.0, seed=11)
+    d_prev = np.zeros(theta.size)
+    lam = 1.0
+    fs = [orc.loss(theta, dims, cfg.C, X, Y)]
+    used_prev = False
+    for k in range(4):
+        S = np.random.default_rng(100 + k).permutation(60)[:20]
+        out = orc.newton_step(theta, dims, cfg.C, X, Y, S, d_prev, lam, cg_max=30, sigma=1e-3, blockdiag=blockdiag)
+        assert abs(out["f_old"] - fs[-1]) <= 1e-13 * abs(fs[-1])
+        assert out["alpha"] > 0 and out["f_new"] <= out["f_old"] + 1e-4 * out["alpha"] * out["gTd"]
+        assert out["gTd"] < 0
+        np.testing.assert_allclose(out["theta"], theta + out["alpha"] * out["d"], rtol=1e-14, atol=1e-16)
+        rho = (out["f_new"] - out["f_old"]) / (out["alpha"] * out["gTd"] + 0.5 * out["alpha"] ** 2 * out["dGd"])
+        assert abs(rho - out["rho"]) <= 1e-12 * abs(rho)
+        assert out["lam"] == orc.lm_update(lam, rho)
+        # d'Gd reported for the combined direction is the quadratic form of the whole matrix
+        Gd = orc.gn_matvec(theta, dims, cfg.C, X[S], out["d"])
+        assert abs(out["d"] @ Gd - out["dGd"]) <= 1e-9 * abs(out["dGd"])
+        if k == 0:
+            assert out["beta"] == (1.0, 0.0)
+        used_prev |= out["beta"][1] != 0.0
+        theta, d_prev, lam = out["theta"], out["d"], out["lam"]
+        fs.append(out["f_new"])
+    assert all(b < a for a, b in zip(fs, fs[1:]))
+    assert used_prev
+
+
 # ------------------------------------------------------------------ inputs
 
 def test_input_generator_shapes_and_ranges():
