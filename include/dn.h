@@ -132,6 +132,52 @@ int dn_cg(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter
           float* d, int* iters_host, double* resnorm_host);
 
 /*
+ * One iteration of the subsampled Newton method (Section 4.5, the algorithm that summarises the
+ * procedure, for one partition that owns every variable):
+ *   1. g = grad f(theta) and f(theta) on all l rows;
+ *   2. dn_jacobian_prep on the rows S (the subsample S_k of this iteration, chosen by the caller);
+ *   3. d = CG solution of (G^S + lambda I) d = -g, whole matrix or per-layer blocks (params->mode),
+ *      stopped by params->sigma or after params->cg_max iterations;
+ *   4. if params->combine: d <- beta1 d + beta2 d_prev, (beta1, beta2) minimising
+ *      1/2 u^T G^S u + g^T u over u = beta1 d + beta2 d_prev with the WHOLE G^S (two extra products);
+ *      (beta1, beta2) = (1, 0) when the determinant of the 2x2 system is <= params->eps (Section 4.3);
+ *   5. backtracking line search: the largest alpha in {1, 1/2, 1/4, ...} (at most params->max_trials
+ *      candidates) with f(theta + alpha d) <= f(theta) + eta alpha g^T d;
+ *   6. rho = (f(theta + alpha d) - f(theta)) / (alpha g^T d + alpha^2/2 d^T G^S d);
+ *      lambda <- lambda*drop if rho > 0.75, unchanged if 0.25 <= rho <= 0.75, else lambda*boost.
+ * theta (device, n floats) is advanced in place to theta + alpha d; d_prev (device, n floats; zeros before
+ * the first iteration) receives the direction taken; params->lambda receives the next lambda.
+ * If no candidate step is accepted, theta is left unchanged, alpha = 0 is reported and lambda is boosted.
+ * The 2x2 system, the step-size test and the lambda rule are evaluated on the host in fp64 from dot
+ * products accumulated in fp64 on the device.  The call synchronises the stream several times.
+ * X is [l x n_0], Y is [l x n_L], S holds s row indices (device), as in dn_grad / dn_jacobian_prep.
+ */
+typedef struct dn_newton_params {
+    double lambda;      /* in: lambda_k; out: lambda_{k+1} */
+    double sigma;       /* CG stopping tolerance (0: run cg_max iterations) */
+    double eta;         /* sufficient-decrease constant, 0 < eta < 1 */
+    double eps;         /* determinant threshold of the two-variable system */
+    double drop, boost; /* factors of the lambda rule, 0 < drop <= 1 <= boost */
+    int cg_max;         /* >= 1 */
+    int mode;           /* DN_FULL or DN_BLOCKDIAG: matrix of the CG systems */
+    int combine;        /* nonzero: step 4 */
+    int max_trials;     /* >= 1 */
+} dn_newton_params;
+
+typedef struct dn_newton_stats {
+    double f_old, f_new;   /* f(theta) before and after the step */
+    double alpha;          /* accepted step size, 0 if none */
+    double beta1, beta2;   /* combination coefficients ((1,0) if not combined) */
+    double rho;            /* actual / predicted reduction */
+    double gTd, dGd;       /* g^T d and d^T G^S d of the direction taken */
+    int cg_iters;          /* CG iterations run */
+    int f_evals;           /* objective evaluations of the line search */
+} dn_newton_stats;
+
+int dn_newton_step(dn_ctx* ctx, float* theta, const float* X, const float* Y, int l, const int* S, int s,
+                   float* d_prev, dn_newton_params* params, dn_newton_stats* stats_host);
+
+/*
  * Kernel timing.  With profiling enabled every launch of the library's kernels is bracketed
  * by HIP events on the bound stream; dn_profile_read returns, for kernel class `which`
  * (0 <= which < dn_profile_num_classes()), the summed duration in milliseconds and the

@@ -21,6 +21,22 @@ _LIB: Optional[ctypes.CDLL] = None
 _c_float_p = ctypes.c_void_p  # device pointers travel as integers
 
 
+class NewtonParams(ctypes.Structure):
+    """dn_newton_params of include/dn.h."""
+    _fields_ = [("lam", ctypes.c_double), ("sigma", ctypes.c_double), ("eta", ctypes.c_double),
+                ("eps", ctypes.c_double), ("drop", ctypes.c_double), ("boost", ctypes.c_double),
+                ("cg_max", ctypes.c_int), ("mode", ctypes.c_int), ("combine", ctypes.c_int),
+                ("max_trials", ctypes.c_int)]
+
+
+class NewtonStats(ctypes.Structure):
+    """dn_newton_stats of include/dn.h."""
+    _fields_ = [("f_old", ctypes.c_double), ("f_new", ctypes.c_double), ("alpha", ctypes.c_double),
+                ("beta1", ctypes.c_double), ("beta2", ctypes.c_double), ("rho", ctypes.c_double),
+                ("gTd", ctypes.c_double), ("dGd", ctypes.c_double), ("cg_iters", ctypes.c_int),
+                ("f_evals", ctypes.c_int)]
+
+
 class DnError(RuntimeError):
     def __init__(self, code: int, where: str, hip: int = 0):
         self.code = code
@@ -58,6 +74,7 @@ def load_library() -> ctypes.CDLL:
         "dn_jacobian_read": (i, [vp, i, vp]),
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
+        "dn_newton_step": (i, [vp, vp, vp, vp, i, vp, i, vp, P(NewtonParams), P(NewtonStats)]),
         "dn_profile_enable": (i, [vp, i]),
         "dn_profile_select": (i, [vp, ctypes.c_ulonglong]),
         "dn_profile_reset": (i, [vp]),
@@ -76,7 +93,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_profile_enable",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_newton_step", "dn_profile_enable",
     "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
 )
@@ -209,3 +226,26 @@ def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int
                         _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
     ctx._check(rc, "dn_cg")
     return iters.value, [res[k] for k in range(nres)]
+
+
+def dn_newton_step(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor, S: torch.Tensor,
+                   d_prev: torch.Tensor, lam: float, cg_max: int, sigma: float = 1e-3, eta: float = 1e-4,
+                   eps: float = 1e-5, drop: float = 2.0 / 3.0, boost: float = 1.5, mode: int = DN_FULL,
+                   combine: bool = True, max_trials: int = 30) -> dict:
+    """One outer Newton iteration (Section 4.5): theta and d_prev are updated in place; returns the
+    statistics of the step and the next lambda under key "lam"."""
+    if not (S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()):
+        raise TypeError("S: need a contiguous int32 device tensor")
+    l = X.shape[0]
+    prm = NewtonParams(float(lam), float(sigma), float(eta), float(eps), float(drop), float(boost), int(cg_max),
+                       int(mode), int(bool(combine)), int(max_trials))
+    st = NewtonStats()
+    rc = ctx._lib.dn_newton_step(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
+                                 _dev_f32(Y, "Y", l * ctx.dims[-1]), l, S.data_ptr(), S.numel(),
+                                 _dev_f32(d_prev, "d_prev", ctx.n), ctypes.byref(prm), ctypes.byref(st))
+    ctx._check(rc, "dn_newton_step")
+    ctx.s = S.numel()
+    out = {name: getattr(st, name) for name, _ in NewtonStats._fields_}
+    out["beta"] = (st.beta1, st.beta2)
+    out["lam"] = prm.lam
+    return out

@@ -546,4 +546,45 @@ __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const
     for (long long e = lo + threadIdx.x; e < hi; e += 256) p[e] = r[e] + beta * p[e];
 }
 
+// ---------------------------------------------------------------------------------------------
+// Outer Newton iteration (Section 4.3 direction combination, Section 4.5 line search): vector kernels.
+
+// Partial sums of the five inner products of the two-variable system and of the step-size test:
+//   0: g^T d   1: g^T db   2: d^T Gd   3: db^T Gd   4: db^T Gdb        partials[k * gridDim.x + block]
+__global__ __launch_bounds__(256) void newton_dots_kernel(const float* __restrict__ g, const float* __restrict__ d,
+                                                          const float* __restrict__ db,
+                                                          const float* __restrict__ Gd,
+                                                          const float* __restrict__ Gdb, long long n,
+                                                          double* __restrict__ partials) {
+    __shared__ double red[4];
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0, a4 = 0.0;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256) {
+        const double ge = g[e], de = d[e], be = db[e], gd = Gd[e], gb = Gdb[e];
+        a0 += ge * de; a1 += ge * be; a2 += de * gd; a3 += be * gd; a4 += be * gb;
+    }
+    const double v[5] = {a0, a1, a2, a3, a4};
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+        const double t = block_sum_d(v[k], red);
+        if (threadIdx.x == 0) partials[(long long)k * gridDim.x + blockIdx.x] = t;
+    }
+}
+
+// out[k] = sum of partials[k * nblocks .. (k+1) * nblocks), fixed order
+__global__ __launch_bounds__(256) void newton_dots_finalize_kernel(const double* __restrict__ partials, int nblocks,
+                                                                   double* __restrict__ out) {
+    __shared__ double red[4];
+    for (int k = 0; k < 5; ++k) {
+        const double t = block_sum_range(partials, k * nblocks, (k + 1) * nblocks, red);
+        if (threadIdx.x == 0) out[k] = t;
+    }
+}
+
+// out = a x + b y   (out may alias x or y)
+__global__ __launch_bounds__(256) void axpby_kernel(float a, const float* x, float b, const float* y, float* out,
+                                                    long long n) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256)
+        out[e] = a * x[e] + b * y[e];
+}
+
 }  // namespace dn

@@ -85,6 +85,8 @@ struct dn_ctx {
     size_t o_AL = 0;
     size_t o_WT = 0;           // W^m = (A^m)^T for m = 2..L, dense, at the theta offsets of A^m
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
+    // outer Newton iteration: gradient, direction, G d, G d_prev, trial point; partial sums of 5 dot products
+    size_t o_ng = 0, o_nd = 0, o_nGd = 0, o_nGdb = 0, o_ntheta = 0, o_npart = 0;
     long long tn_floats = 0;
 
     char* ws = nullptr;
@@ -316,6 +318,12 @@ void layout_workspace(dn_ctx* c) {
     for (int k = 0; k < 3; ++k) c->o_part[k] = take(cur, sizeof(double) * DN_MAX_PARTIALS);
     c->o_state = take(cur, 2 * sizeof(CgState));
     c->o_f = take(cur, 256);
+    c->o_ng = take(cur, nvec);
+    c->o_nd = take(cur, nvec);
+    c->o_nGd = take(cur, nvec);
+    c->o_nGdb = take(cur, nvec);
+    c->o_ntheta = take(cur, nvec);
+    c->o_npart = take(cur, sizeof(double) * 5 * DN_MAX_PARTIALS);
     c->ws_bytes = cur;
 }
 
@@ -882,6 +890,122 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
     DN_HIP(c, hipStreamSynchronize(c->stream));
     *iters_host = iters;
     for (int k = 0; k < sg.nseg; ++k) resnorm_host[k] = std::sqrt(hst.rho[k]);
+    return DN_OK;
+}
+
+int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int l, const int* S, int s, float* d_prev,
+                   dn_newton_params* prm, dn_newton_stats* st) {
+    if (!c || !theta || !X || !Y || !S || !d_prev || !prm || !st || l < 1 || l > c->l_max || s < 1 || s > c->s_max)
+        return DN_EINVAL;
+    if (bad_mode(prm->mode) || prm->cg_max < 1 || prm->max_trials < 1 || !(prm->lambda >= 0.0) ||
+        !(prm->sigma >= 0.0) || !(prm->eta > 0.0 && prm->eta < 1.0) || !(prm->drop > 0.0 && prm->drop <= 1.0) ||
+        !(prm->boost >= 1.0))
+        return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    std::memset(st, 0, sizeof(*st));
+    const long long n = c->n;
+    float* g = c->fptr(c->o_ng);
+    float* d = c->fptr(c->o_nd);
+    float* Gd = c->fptr(c->o_nGd);
+    float* Gdb = c->fptr(c->o_nGdb);
+    float* trial = c->fptr(c->o_ntheta);
+    double* part = c->dptr(c->o_npart);
+    double* dots_dev = c->dptr(c->o_f) + 8;
+    const int vgrid = grid_for(n);
+    const int dgrid = std::min(DN_MAX_PARTIALS, vgrid);
+
+    // 1-3: gradient on all rows, Jacobian blocks on S, CG direction
+    double f0 = 0.0;
+    int rc = dn_grad(c, theta, X, Y, l, g, &f0);
+    if (rc != DN_OK) return rc;
+    rc = dn_jacobian_prep(c, theta, X, l, S, s);
+    if (rc != DN_OK) return rc;
+    double resn[DN_MAX_LAYERS];
+    rc = dn_cg(c, g, prm->lambda, prm->sigma, prm->cg_max, prm->mode, d, &st->cg_iters, resn);
+    if (rc != DN_OK) return rc;
+
+    // 4: inner products with the whole G^S
+    rc = gn_matvec(c, d, Gd, DN_FULL);
+    if (rc != DN_OK) return rc;
+    const float* db = prm->combine ? d_prev : d;        // without combination the d_prev slots repeat d
+    if (prm->combine) {
+        rc = gn_matvec(c, d_prev, Gdb, DN_FULL);
+        if (rc != DN_OK) return rc;
+    }
+    double dots[5];
+    {
+        ProfScope ps(c, KC_CG_VEC);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(newton_dots_kernel, dim3(dgrid), dim3(256), 0, c->stream, g, d, db, Gd,
+                           prm->combine ? Gdb : Gd, n, part);
+        DN_HIP(c, hipGetLastError());
+        hipLaunchKernelGGL(newton_dots_finalize_kernel, dim3(1), dim3(256), 0, c->stream, part, dgrid, dots_dev);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    DN_HIP(c, hipMemcpyAsync(dots, dots_dev, sizeof(dots), hipMemcpyDeviceToHost, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    double beta1 = 1.0, beta2 = 0.0;
+    const double a11 = dots[2], a12 = dots[3], a22 = dots[4];
+    if (prm->combine) {
+        const double b1 = -dots[0], b2 = -dots[1];
+        const double det = a11 * a22 - a12 * a12;
+        if (det > prm->eps) {
+            beta1 = (b1 * a22 - b2 * a12) / det;
+            beta2 = (a11 * b2 - a12 * b1) / det;
+        }
+    }
+    double gTd = dots[0], dGd = a11;
+    if (beta1 != 1.0 || beta2 != 0.0) {
+        ProfScope ps(c, KC_CG_VEC);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(axpby_kernel, dim3(vgrid), dim3(256), 0, c->stream, (float)beta1, d, (float)beta2, d_prev,
+                           d, n);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+        gTd = beta1 * dots[0] + beta2 * dots[1];
+        dGd = beta1 * beta1 * a11 + 2.0 * beta1 * beta2 * a12 + beta2 * beta2 * a22;
+    }
+    st->beta1 = beta1; st->beta2 = beta2; st->gTd = gTd; st->dGd = dGd; st->f_old = f0;
+
+    // 5: backtracking line search on f
+    double alpha = 1.0, f_new = f0;
+    bool accepted = false;
+    for (int k = 0; k < prm->max_trials; ++k) {
+        {
+            ProfScope ps(c, KC_CG_VEC);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(axpby_kernel, dim3(vgrid), dim3(256), 0, c->stream, 1.0f, theta, (float)alpha, d, trial,
+                               n);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+        double f_try = 0.0;
+        rc = dn_forward(c, trial, X, Y, l, &f_try, nullptr);
+        if (rc != DN_OK) return rc;
+        st->f_evals = k + 1;
+        if (f_try <= f0 + prm->eta * alpha * gTd) {
+            f_new = f_try;
+            accepted = true;
+            break;
+        }
+        alpha *= 0.5;
+    }
+    // 6: ratio of actual to predicted reduction, next lambda; advance theta, remember the direction
+    if (accepted) {
+        st->alpha = alpha;
+        st->rho = (f_new - f0) / (alpha * gTd + 0.5 * alpha * alpha * dGd);
+        if (st->rho > 0.75) prm->lambda *= prm->drop;
+        else if (!(st->rho >= 0.25)) prm->lambda *= prm->boost;
+        DN_HIP(c, hipMemcpyAsync(theta, trial, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c->stream));
+    } else {
+        st->alpha = 0.0;
+        st->rho = 0.0;
+        prm->lambda *= prm->boost;
+    }
+    st->f_new = f_new;
+    DN_HIP(c, hipMemcpyAsync(d_prev, d, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
     return DN_OK;
 }
 

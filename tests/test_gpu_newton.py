@@ -1,0 +1,122 @@
+"""GPU parity of the outer Newton iteration (dn_newton_step) against the oracle's newton_step.
+
+Each iteration is compared on its own: the oracle is restarted from the device's current theta and previous
+direction, so a difference seen at iteration k belongs to iteration k.  Discrete outcomes (step size, number
+of objective evaluations, CG iteration count, which branch of the lambda rule) must be equal; the test
+workloads keep every decision away from its threshold.  Continuous outcomes: the direction is a CG iterate
+and gets the CG bar, 1e-3 relative L2; everything computed from it inherits that bar on the part it drives:
+theta within 1e-3 of the step length (plus fp32 rounding of theta itself), f(theta + alpha d) within
+1e-4 |f| plus 2e-3 of the change of f over the step, beta and g^T d within 1e-3, d^T G d within 2e-3,
+rho within 1e-2 absolute.
+A free-running comparison of the objective over the same iterations follows with a looser bar.
+"""
+import numpy as np
+import pytest
+import torch
+
+import dn_inputs
+import paper_1802_00130_amd as dn
+from oracle import dn_oracle as orc
+from tests.gpu_common import Workload, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+# name: (configuration, lambda_1, CG iterations, scale of the initial theta, Newton iterations)
+CASES = {
+    "cfg1": (lambda: dn_inputs.config(1), 1.0, 8, 1.0, 3),
+    "mid_60-40-30-5": (lambda: dn_inputs.custom((60, 40, 30, 5), l=900, s=300, C=20.0, seed=31), 1.0, 12, 1.0, 3),
+    "twopass_24-20-18-20": (lambda: dn_inputs.custom((24, 20, 18, 20), l=400, s=150, C=8.0, seed=32), 0.5, 10, 1.0, 3),
+    "L1_12-4": (lambda: dn_inputs.custom((12, 4), l=200, s=80, C=3.0, seed=33), 0.1, 20, 1.0, 3),
+    # saturated start, tiny subsample, weak damping: the quadratic model overshoots, so the line search
+    # halves several times and the lambda rule leaves its "drop" branch.  Few CG iterations: on
+    # systems this small CG converges within a handful of steps, after which an fp32 recurrence only
+    # amplifies rounding noise and no longer tracks the fp64 iterates (seen alike in a CPU emulation that
+    # rounds the CG vectors to fp32)
+    "harsh_8-6-4": (lambda: dn_inputs.custom((8, 6, 4), l=60, s=6, C=50.0, seed=51), 1e-2, 3, 4.0, 3),
+    "harsh_12-10-8-3": (lambda: dn_inputs.custom((12, 10, 8, 3), l=120, s=8, C=100.0, seed=52), 1e-3, 3, 5.0, 3),
+}
+
+
+def _subset(cfg, k):
+    return np.random.default_rng(cfg.seed * 1000 + k).permutation(cfg.l)[:cfg.s].astype(np.int32)
+
+
+@pytest.mark.parametrize("mode", [dn.DN_FULL, dn.DN_BLOCKDIAG])
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_newton_iterations(name, mode):
+    make, lam0, cg_max, scale, iterations = CASES[name]
+    cfg = make()
+    print(f"[case] {name} mode {mode}", flush=True)
+    w = Workload(cfg, bias_scale=0.2)
+    w.theta = (scale * w.theta).astype(np.float32)
+    w.dtheta = torch.from_numpy(w.theta).to("cuda:0")
+    X64, Y64 = w.X.astype(np.float64), w.Y.astype(np.float64)
+    theta = w.dtheta.clone()
+    d_prev = torch.zeros_like(theta)
+    lam = lam0
+    theta_free = w.theta.astype(np.float64)       # oracle trajectory that never sees the device's iterates
+    dprev_free = np.zeros(w.n)
+    lam_free = lam0
+    combined = False
+    halved = False
+    for k in range(iterations):
+        S = _subset(cfg, k)
+        th_in = theta.cpu().numpy().astype(np.float64)
+        dp_in = d_prev.cpu().numpy().astype(np.float64)
+        out = dn.dn_newton_step(w.ctx, theta, w.dX, w.dY, torch.from_numpy(S).to("cuda:0"), d_prev, lam, cg_max,
+                                sigma=0.0, mode=mode)
+        ref = orc.newton_step(th_in, cfg.dims, cfg.C, X64, Y64, S, dp_in, lam, cg_max, sigma=0.0,
+                              blockdiag=(mode == dn.DN_BLOCKDIAG))
+        print(f"  k={k}: f {out['f_old']:.6f} -> {out['f_new']:.6f} (oracle {ref['f_new']:.6f}), alpha {out['alpha']}, "
+              f"beta ({out['beta1']:.4f}, {out['beta2']:.4f}), rho {out['rho']:.4f}, lambda -> {out['lam']:.4f}", flush=True)
+        assert out["alpha"] == ref["alpha"] and out["alpha"] > 0
+        assert out["f_evals"] == ref["f_evals"] and out["cg_iters"] == ref["cg_iters"]
+        assert abs(out["f_old"] - ref["f_old"]) <= 1e-4 * abs(ref["f_old"])
+        step = abs(ref["f_new"] - ref["f_old"])
+        e_d = rel_l2(d_prev.cpu().numpy(), ref["d"])
+        e_th = np.linalg.norm(theta.cpu().numpy().astype(np.float64) - ref["theta"])
+        print(f"       errors: d {e_d:.1e}, theta {e_th / np.linalg.norm(ref['theta'] - th_in):.1e} of the step, "
+              f"f_new {abs(out['f_new'] - ref['f_new']) / abs(ref['f_new']):.1e}, rho {abs(out['rho'] - ref['rho']):.1e}",
+              flush=True)
+        assert abs(out["f_new"] - ref["f_new"]) <= 1e-4 * abs(ref["f_new"]) + 2e-3 * step
+        assert e_d <= 1e-3
+        assert e_th <= 1e-3 * np.linalg.norm(ref["theta"] - th_in) + 1e-6 * np.linalg.norm(ref["theta"])
+        assert rel_l2(out["beta"], ref["beta"]) <= 1e-3
+        assert abs(out["gTd"] - ref["gTd"]) <= 1e-3 * abs(ref["gTd"])
+        assert abs(out["dGd"] - ref["dGd"]) <= 2e-3 * abs(ref["dGd"])
+        assert abs(out["rho"] - ref["rho"]) <= 1e-2
+        assert out["lam"] == pytest.approx(ref["lam"], rel=1e-12)
+        if k == 0:
+            assert out["beta"] == (1.0, 0.0)
+        combined |= out["beta2"] != 0.0
+        halved |= out["alpha"] < 1.0
+        lam = out["lam"]
+        free = orc.newton_step(theta_free, cfg.dims, cfg.C, X64, Y64, S, dprev_free, lam_free, cg_max, sigma=0.0,
+                               blockdiag=(mode == dn.DN_BLOCKDIAG))
+        theta_free, dprev_free, lam_free = free["theta"], free["d"], free["lam"]
+        if not name.startswith("harsh"):     # overshooting steps amplify differences from one iteration to the next
+            assert abs(out["f_new"] - free["f_new"]) <= 1e-3 * abs(free["f_new"]) + 1e-2 * abs(free["f_new"] - free["f_old"])
+    assert combined
+    # which runs see a step size below 1 (known from the oracle's trajectory)
+    assert halved == (name == "harsh_8-6-4" or (name == "harsh_12-10-8-3" and mode == dn.DN_BLOCKDIAG))
+    w.ctx.close()
+
+
+def test_newton_step_without_combination_and_with_cg_tolerance():
+    cfg = dn_inputs.custom((30, 16, 6), l=300, s=120, C=10.0, seed=41)
+    w = Workload(cfg, bias_scale=0.2)
+    X64, Y64 = w.X.astype(np.float64), w.Y.astype(np.float64)
+    theta = w.dtheta.clone()
+    d_prev = torch.zeros_like(theta)
+    S = _subset(cfg, 0)
+    out = dn.dn_newton_step(w.ctx, theta, w.dX, w.dY, torch.from_numpy(S).to("cuda:0"), d_prev, 1.0, 200,
+                            sigma=1e-2, combine=False, drop=0.5, boost=3.0)
+    ref = orc.newton_step(w.theta.astype(np.float64), cfg.dims, cfg.C, X64, Y64, S, np.zeros(w.n), 1.0, 200,
+                          sigma=1e-2, combine=False, drop=0.5, boost=3.0)
+    assert out["cg_iters"] == ref["cg_iters"] and 1 < out["cg_iters"] < 200
+    assert out["alpha"] == ref["alpha"] and out["beta"] == (1.0, 0.0)
+    assert abs(out["f_new"] - ref["f_new"]) <= 1e-4 * abs(ref["f_new"])
+    assert abs(out["dGd"] - ref["dGd"]) <= 2e-3 * abs(ref["dGd"])
+    assert out["lam"] == pytest.approx(ref["lam"], rel=1e-12)
+    assert rel_l2(theta.cpu().numpy(), ref["theta"]) <= 1e-4
+    w.ctx.close()
