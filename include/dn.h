@@ -39,7 +39,8 @@ enum {
     DN_ENOSPC = -2,   /* workspace given to dn_bind is smaller than dn_workspace_bytes() */
     DN_ESTATE = -3,   /* call needs a bound workspace / a prior dn_jacobian_prep and there is none */
     DN_EHIP = -4,     /* a HIP runtime call failed; dn_last_hip_error() gives the HIP code */
-    DN_ENOMEM = -5    /* host allocation failed */
+    DN_ENOMEM = -5,   /* host allocation failed */
+    DN_ETIMEOUT = -6  /* a bounded wait between work-groups of a kernel ran out (see dn_sync_status) */
 };
 
 /* mode of dn_gn_matvec and dn_cg */
@@ -176,6 +177,21 @@ typedef struct dn_newton_stats {
 
 int dn_newton_step(dn_ctx* ctx, float* theta, const float* X, const float* Y, int l, const int* S, int s,
                    float* d_prev, dn_newton_params* params, dn_newton_stats* stats_host);
+
+/*
+ * Products with n_L > 16 and at least two hidden layers read each stored block ONCE per product by
+ * letting a team of work-groups share a sample (the kernel's work-groups wait for each other on
+ * counters in device memory; every wait is bounded).  dn_set_stream_passes(ctx, 2) selects the plain
+ * two-pass kernels instead (one read for J v, one for J^T), 0 restores the automatic choice.
+ * dn_set_spin_limit sets the number of polls after which such a wait gives up (default 1 << 20, a few
+ * seconds); a wait that runs out makes the kernel's work-groups leave, later products do nothing, and
+ * the condition is reported by the next call that synchronises (dn_cg, dn_newton_step, dn_sync_status)
+ * as DN_ETIMEOUT.  It is cleared by dn_bind.
+ */
+int dn_set_stream_passes(dn_ctx* ctx, int passes);
+int dn_set_spin_limit(dn_ctx* ctx, unsigned polls);
+/* Wait for all work enqueued so far; DN_OK, DN_ETIMEOUT (see above) or DN_EHIP. */
+int dn_sync_status(dn_ctx* ctx);
 
 /*
  * Kernel timing.  With profiling enabled every launch of the library's kernels is bracketed

@@ -75,6 +75,9 @@ def load_library() -> ctypes.CDLL:
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
         "dn_newton_step": (i, [vp, vp, vp, vp, i, vp, i, vp, P(NewtonParams), P(NewtonStats)]),
+        "dn_set_stream_passes": (i, [vp, i]),
+        "dn_set_spin_limit": (i, [vp, ctypes.c_uint]),
+        "dn_sync_status": (i, [vp]),
         "dn_profile_enable": (i, [vp, i]),
         "dn_profile_select": (i, [vp, ctypes.c_ulonglong]),
         "dn_profile_reset": (i, [vp]),
@@ -93,7 +96,8 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_newton_step", "dn_profile_enable",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
+    "dn_profile_enable",
     "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
 )
@@ -145,6 +149,23 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    # -- single-pass (team) kernel controls --------------------------------------------------
+    def set_stream_passes(self, passes: int) -> None:
+        """0: automatic (one read of the stored blocks where available); 2: always the two-pass kernels."""
+        self._check(self._lib.dn_set_stream_passes(self._h, int(passes)), "dn_set_stream_passes")
+
+    def set_spin_limit(self, polls: int) -> None:
+        self._check(self._lib.dn_set_spin_limit(self._h, int(polls)), "dn_set_spin_limit")
+
+    def sync_status(self) -> int:
+        """Wait for the stream; returns the library's status code (0, or DN_ETIMEOUT = -6) without raising."""
+        return int(self._lib.dn_sync_status(self._h))
+
+    def rebind(self) -> None:
+        """Bind the same workspace again (clears a reported time-out and the stored Jacobian)."""
+        self._check(self._lib.dn_bind(self._h, self._ws_ptr, self.workspace_bytes, self.stream.cuda_stream), "dn_bind")
+        self.s = 0
 
     # -- profiling ---------------------------------------------------------------------------
     def profile_enable(self, on: bool) -> None:

@@ -24,6 +24,12 @@ constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
 constexpr int kBKmax = 32;
 // tile rows per super-row of the tile walk: 8 x 8 tiles are about what one XCD (32 CUs) holds at a time
 constexpr int kGroupM = 8;
+// most work-groups of 256 threads a launch can have resident on the chip (256 CUs x 2048 threads / 256);
+// sizes the exchange buffers of the team kernel
+constexpr int kMaxResidentWGs = 2048;
+// 64-bit words in each exchange region of the team kernel: teams x 2 sets x (work-groups per team) x
+// (at most 128 rows per work-group), teams x work-groups <= kMaxResidentWGs
+constexpr long long kTeamExchWords = 2LL * kMaxResidentWGs * 128;
 
 enum KernelClass {
     KC_GEMM_FWD = 0,      // forward layer products (all samples or subsample)
@@ -35,6 +41,7 @@ enum KernelClass {
     KC_JV_JTV_FUSED,      // product: both passes over P, one read
     KC_JV,                // product: P q
     KC_JTV,               // product: P^T r
+    KC_JV_JTV_TEAM,       // product: both passes over P, one read, teams of work-groups
     KC_GEMM_IMPLICIT,     // product: the two small dense products that stand in for block L-1
     KC_TN_REDUCE,         // slice fold + regularisation term
     KC_JAC_INIT,
@@ -46,7 +53,7 @@ enum KernelClass {
 
 const char* const kClassNames[KC_COUNT] = {
     "gemm_forward", "gemm_backprop", "gemm_tn_grad", "gemm_jacobian_prep", "gemm_q_matvec", "gemm_tn_matvec",
-    "jv_jtv_fused", "jv_rows", "jtv_cols", "gemm_implicit_block", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
+    "jv_jtv_fused", "jv_rows", "jtv_cols", "jv_jtv_team", "gemm_implicit_block", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
 
 inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -87,6 +94,10 @@ struct dn_ctx {
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
     // outer Newton iteration: gradient, direction, G d, G d_prev, trial point; partial sums of 5 dot products
     size_t o_ng = 0, o_nd = 0, o_nGd = 0, o_nGdb = 0, o_ntheta = 0, o_npart = 0;
+    // team kernel: partial vectors, folded vectors, counters, error word
+    size_t o_texch = 0, o_terr = 0, o_ttp[DN_MAX_LAYERS + 1] = {0};
+    int team_rpt = 0;               // rows per thread of the team kernel for this n_L (0: team kernel not applicable)
+    int team_nrs = 0;               // row slices
     long long tn_floats = 0;
 
     char* ws = nullptr;
@@ -95,6 +106,14 @@ struct dn_ctx {
     bool prepped = false;
     int s_cur = 0;
     int last_hip = 0;
+    int num_cus = 256;
+    // team kernel (single pass over the stored blocks for n_L > 16)
+    int stream_passes = 0;          // 0 automatic, 2 force the two-pass kernels
+    unsigned spin_limit = 1u << 20;
+    bool team_clean = false;        // exchange words and error word cleared since the last dn_bind
+    bool team_used = false;
+    unsigned team_seq = 0;          // sequence numbers handed out so far
+    int team_wgs_per_cu = 0;        // resident work-groups per CU of the kernel variant (0: not looked up)
 
     // profiling
     bool prof = false;
@@ -324,6 +343,19 @@ void layout_workspace(dn_ctx* c) {
     c->o_nGdb = take(cur, nvec);
     c->o_ntheta = take(cur, nvec);
     c->o_npart = take(cur, sizeof(double) * 5 * DN_MAX_PARTIALS);
+    // team kernel: exchange words (two regions of kTeamExchWords 64-bit words: partial vectors, folded
+    // vectors) and, with several row slices, the per-slice partial transposed products
+    c->team_rpt = 0;
+    c->team_nrs = 0;
+    if (L >= 3 && c->dims[L] > 16) {
+        c->team_rpt = round_up(c->dims[L], 32) <= 64 ? 16 : 32;
+        c->team_nrs = cdiv(c->dims[L], 4 * c->team_rpt);
+        c->o_texch = take(cur, sizeof(unsigned long long) * 2 * kTeamExchWords);
+        if (c->team_nrs > 1)
+            for (int m = 1; m + 1 < L; ++m)
+                c->o_ttp[m] = take(cur, sizeof(float) * (size_t)c->team_nrs * c->s_max * c->ld[m]);
+    }
+    c->o_terr = take(cur, 256);
     c->ws_bytes = cur;
 }
 
@@ -452,6 +484,93 @@ void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
     a.nwslots = w;
 }
 
+// ---- team kernel plumbing ------------------------------------------------------------------
+struct TeamPlan {
+    bool ok = false;
+    TeamArgs ta;
+};
+
+hipError_t plan_team(dn_ctx* c, const StreamArgs& a, TeamPlan& tp) {
+    tp.ok = false;
+    const int L = c->L;
+    if (c->stream_passes == 2 || c->team_rpt == 0) return hipSuccess;
+    if (c->team_wgs_per_cu == 0) {
+        int nb = 0;
+        hipError_t e = c->team_rpt == 16
+                           ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<16, 0, 4>, 256, 0)
+                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<32, 8, 3>, 256, 0);
+        if (e != hipSuccess) return e;
+        c->team_wgs_per_cu = nb >= 1 ? nb : -1;
+    }
+    if (c->team_wgs_per_cu < 1) return hipSuccess;
+    TeamArgs& ta = tp.ta;
+    std::memset(&ta, 0, sizeof(ta));
+    ta.a = a;
+    const int RB = 4 * c->team_rpt;
+    int ncs = 0;
+    for (int m = 1; m + 1 < L; ++m) {
+        ta.slice_begin[m] = ncs;
+        ncs += cdiv(c->dims[m], 256);
+    }
+    const int G = c->team_nrs * ncs;
+    const int resident = std::min(kMaxResidentWGs, c->num_cus * c->team_wgs_per_cu);
+    const int teams = std::min(a.s, resident / G);
+    if (teams < 1) return hipSuccess;
+    ta.G = G;
+    ta.teams = teams;
+    ta.nrs = c->team_nrs;
+    ta.ncs = ncs;
+    ta.ntasks = (RB / 32) * ta.nrs * (a.blockdiag ? (L - 2) : 1);
+    ta.nfolders = std::min(G, ta.ntasks);
+    ta.part = reinterpret_cast<unsigned long long*>(c->ws + c->o_texch);
+    ta.rbar = ta.part + kTeamExchWords;
+    for (int m = 1; m + 1 < L; ++m) ta.tpart[m] = c->team_nrs > 1 ? c->fptr(c->o_ttp[m]) : nullptr;
+    ta.error = reinterpret_cast<unsigned*>(c->ws + c->o_terr);
+    ta.spin_limit = c->spin_limit;
+    tp.ok = true;
+    return hipSuccess;
+}
+
+hipError_t launch_team(dn_ctx* c, TeamPlan& tp) {
+    TeamArgs& ta = tp.ta;
+    const unsigned per_launch = (unsigned)cdiv(ta.a.s, ta.teams) + 1u;
+    if (!c->team_clean || c->team_seq > 0x7fff0000u) {
+        // first use after dn_bind (or the sequence numbers are about to wrap): start from a blank slate
+        hipLaunchKernelGGL(team_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ta.part, 2 * kTeamExchWords,
+                           ta.error);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        c->team_clean = true;
+        c->team_seq = 0;
+    }
+    ta.seq_base = c->team_seq;
+    c->team_seq += per_launch;
+    c->team_used = true;
+    const dim3 grid(ta.teams * ta.G), block(256);
+    if (c->team_rpt == 16) hipLaunchKernelGGL((jv_jtv_team_kernel<16, 0, 4>), grid, block, 0, c->stream, ta);
+    else                   hipLaunchKernelGGL((jv_jtv_team_kernel<32, 8, 3>), grid, block, 0, c->stream, ta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || ta.nrs == 1) return e;
+    // several row slices: add their partial transposed products
+    for (int m = 1; m + 1 < c->L; ++m) {
+        const long long total4 = (long long)ta.a.s * c->ld[m] / 4;
+        hipLaunchKernelGGL(team_fold_t_kernel, dim3(grid_for(total4, 256 * 4)), dim3(256), 0, c->stream, ta.tpart[m],
+                           c->fptr(c->o_T[m]), ta.nrs, total4);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// after a synchronisation: has a wait of the team kernel run out?
+int team_status(dn_ctx* c) {
+    if (!c->team_used) return DN_OK;
+    unsigned err = 0;
+    DN_HIP(c, hipMemcpyAsync(&err, c->ws + c->o_terr, sizeof(err), hipMemcpyDeviceToHost, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    return err ? DN_ETIMEOUT : DN_OK;
+}
+
 // out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
 int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
@@ -512,23 +631,33 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
-        {
-            ProfScope ps(c, KC_JV);
+        TeamPlan tp;
+        DN_HIP(c, plan_team(c, a, tp));
+        if (tp.ok) {
+            // one read of the stored blocks: teams of work-groups, see jv_jtv_team_kernel
+            ProfScope ps(c, KC_JV_JTV_TEAM);
             DN_HIP(c, ps.err);
-            constexpr int UB = 16;
-            hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a);
-            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, launch_team(c, tp));
             DN_HIP(c, ps.end());
-        }
-        {
-            ProfScope ps(c, KC_JTV);
-            DN_HIP(c, ps.err);
-            int chunks = 1;
-            for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
-            hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
-                               sizeof(float) * nL, c->stream, a, chunks);
-            DN_HIP(c, hipGetLastError());
-            DN_HIP(c, ps.end());
+        } else {
+            {
+                ProfScope ps(c, KC_JV);
+                DN_HIP(c, ps.err);
+                constexpr int UB = 16;
+                hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a);
+                DN_HIP(c, hipGetLastError());
+                DN_HIP(c, ps.end());
+            }
+            {
+                ProfScope ps(c, KC_JTV);
+                DN_HIP(c, ps.err);
+                int chunks = 1;
+                for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
+                hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
+                                   sizeof(float) * nL, c->stream, a, chunks);
+                DN_HIP(c, hipGetLastError());
+                DN_HIP(c, ps.end());
+            }
         }
         if (L >= 2) {
             // t^{L-1} = sigma' * (A^L^T 2r):  T^L already holds 2r (full); per-layer uses 2 r^{L-1}
@@ -613,6 +742,7 @@ const char* dn_strerror(int code) {
         case DN_ESTATE: return "call out of order (no workspace bound, or no Jacobian prepared)";
         case DN_EHIP: return "HIP runtime error";
         case DN_ENOMEM: return "host allocation failed";
+        case DN_ETIMEOUT: return "a bounded wait between work-groups ran out";
         default: return "unknown error code";
     }
 }
@@ -672,6 +802,15 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->bound = true;
     c->prepped = false;
+    c->team_clean = false;
+    c->team_used = false;
+    // size of the chip, for kernels whose grid must be resident all at once (default kept if no device answers)
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        c->num_cus = cus;
+    else
+        (void)hipGetLastError();
     return DN_OK;
 }
 
@@ -890,7 +1029,7 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
     DN_HIP(c, hipStreamSynchronize(c->stream));
     *iters_host = iters;
     for (int k = 0; k < sg.nseg; ++k) resnorm_host[k] = std::sqrt(hst.rho[k]);
-    return DN_OK;
+    return team_status(c);
 }
 
 int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int l, const int* S, int s, float* d_prev,
@@ -1006,7 +1145,26 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
     st->f_new = f_new;
     DN_HIP(c, hipMemcpyAsync(d_prev, d, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c->stream));
     DN_HIP(c, hipStreamSynchronize(c->stream));
+    return team_status(c);
+}
+
+int dn_set_stream_passes(dn_ctx* c, int passes) {
+    if (!c || (passes != 0 && passes != 2)) return DN_EINVAL;
+    c->stream_passes = passes;
     return DN_OK;
+}
+
+int dn_set_spin_limit(dn_ctx* c, unsigned polls) {
+    if (!c) return DN_EINVAL;
+    c->spin_limit = polls;
+    return DN_OK;
+}
+
+int dn_sync_status(dn_ctx* c) {
+    if (!c) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    return team_status(c);
 }
 
 int dn_profile_enable(dn_ctx* c, int on) {

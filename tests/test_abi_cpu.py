@@ -88,6 +88,10 @@ def test_call_order_and_argument_errors(lib):
         setattr(prm, field, good)
     assert lib.dn_newton_step(h, fake, fake, fake, 10, fake, 11, fake, ctypes.byref(prm), ctypes.byref(st)) == -1
     assert lib.dn_newton_step(h, fake, fake, fake, 10, fake, 5, fake, None, ctypes.byref(st)) == -1
+    assert lib.dn_set_stream_passes(h, 1) == -1 and lib.dn_set_stream_passes(h, 2) == 0
+    assert lib.dn_set_stream_passes(None, 0) == -1 and lib.dn_set_spin_limit(None, 5) == -1
+    assert lib.dn_set_spin_limit(h, 5) == 0
+    assert lib.dn_strerror(-6).decode().startswith("a bounded wait")
     assert lib.dn_strerror(-2).decode() == "workspace too small"
     assert lib.dn_profile_num_classes() >= 10 and lib.dn_profile_class_name(0).decode() == "gemm_forward"
     lib.dn_destroy(h)
