@@ -188,6 +188,7 @@ struct StreamArgs {
     long long ld[DN_MAX_LAYERS + 1];     // row stride of Z/Q/T/P rows of layer m
     const float* P[DN_MAX_LAYERS + 1];   // P[m], m = 1..L-1: [s][nL][ld[m]]
     const float* Q[DN_MAX_LAYERS + 1];   // Q[m], m = 1..L: [s][ld[m]]
+    const float* Qb[DN_MAX_LAYERS + 1];  // nullable: second half of a Q[m] whose sum over t was cut in two (fused kernel only)
     float* T[DN_MAX_LAYERS + 1];         // T[m], m = 1..L: [s][ld[m]]
     float* R;                            // [L][s][ldr] (full mode uses slot 0 only)
     long long ldr;
@@ -305,6 +306,10 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
     float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
     const float* __restrict__ pbase = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
     if (live) q4 = *reinterpret_cast<const float4*>(a.Q[m] + (long long)i * a.ld[m] + j);
+    if (live && a.Qb[m]) {
+        const float4 qb = *reinterpret_cast<const float4*>(a.Qb[m] + (long long)i * a.ld[m] + j);
+        q4.x += qb.x; q4.y += qb.y; q4.z += qb.z; q4.w += qb.w;
+    }
     // padding columns of Q are never written; mask them
     if (live) {
         const int rem = a.n[m] - j;
