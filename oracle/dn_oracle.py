@@ -203,7 +203,7 @@ def gn_matvec_blockdiag(theta, dims, C, XS, v):
 
 # --------------------------------------------------------------------------- CG
 
-def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history=False):
+def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history=False, cg_min=0, r_percent=None):
     """Conjugate gradient on (G^S + lam I) d = -g  (Sections 2.2, 4.3).
 
     d_0 = 0, r_0 = -g, p_0 = r_0, no preconditioner.  After each step the recurrence
@@ -211,6 +211,11 @@ def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history
     blockdiag=True the L per-layer systems are solved independently, each block with
     its own step lengths and its own stopping test; a block that has met its test is
     left unchanged afterwards.
+
+    r_percent (block-diagonal systems only, Section 4.4): the early termination that spares the blocks still
+    running from holding up the others: all blocks stop after the first iteration k >= cg_min at which the
+    number of blocks that have met their own test is at least r_percent/100 of the number of blocks.  The
+    blocks advance in lock-step here, so "every partition has done cg_min iterations" is k >= cg_min.
 
     Returns (d, iterations, residual norms); residual norms has one entry (full) or one
     per layer (block-diagonal).  With history=True also the list of iterates d_1, d_2, ...
@@ -246,6 +251,8 @@ def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history
         iters += 1
         if history:
             hist.append(d.copy())
+        if r_percent is not None and iters >= cg_min and np.count_nonzero(~active) >= r_percent / 100.0 * len(blocks):
+            break
     res = np.sqrt(rho)
     if history:
         return d, iters, res, hist
@@ -333,7 +340,7 @@ def lm_update(lam, rho, drop=2.0 / 3.0, boost=1.5):
 
 
 def newton_step(theta, dims, C, X, Y, S, d_prev, lam, cg_max, sigma=1e-3, eta=1e-4, eps=1e-5,
-                drop=2.0 / 3.0, boost=1.5, blockdiag=False, combine=True, max_trials=30):
+                drop=2.0 / 3.0, boost=1.5, blockdiag=False, combine=True, max_trials=30, cg_min=0, r_percent=None):
     """One iteration of the subsampled Newton method (Section 4.5, the algorithm summarising the
     procedure, for a single partition owning every variable):
 
@@ -350,7 +357,8 @@ def newton_step(theta, dims, C, X, Y, S, d_prev, lam, cg_max, sigma=1e-3, eta=1e
     Y = np.asarray(Y, dtype=np.float64)
     XS = X[np.asarray(S)]
     g, f0 = grad(theta, dims, C, X, Y)
-    d, iters, _ = cg(theta, dims, C, XS, g, lam, cg_max, sigma=sigma, blockdiag=blockdiag)
+    d, iters, _ = cg(theta, dims, C, XS, g, lam, cg_max, sigma=sigma, blockdiag=blockdiag, cg_min=cg_min,
+                     r_percent=r_percent if blockdiag else None)
     if combine:
         beta1, beta2, (a11, a12, a22) = combine_directions(theta, dims, C, XS, g, d, d_prev, eps)
         d = beta1 * d + beta2 * np.asarray(d_prev, dtype=np.float64)

@@ -329,6 +329,47 @@ def test_cg_blockdiag_blocks_stop_independently():
         np.testing.assert_allclose(d[b], dk[b], rtol=1e-12, atol=1e-15)
 
 
+def test_cg_early_termination_across_blocks():
+    # catches: the percentage applied to running instead of finished blocks, cg_min ignored, a finished block
+    # still being updated, the rule leaking into the single-system mode
+    dims = (12, 10, 8, 3)
+    cfg, X, Y, theta, S = _tiny(dims, l=80, s=60, C=100.0, seed=23)
+    XS = X[S]
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    blocks = orc.block_slices(dims)
+    lam, sigma = 1e-3, 1e-6
+    # iteration at which each block meets its own test when run alone (independent of the rule under test)
+    own = []
+    for b in blocks:
+        gk = np.zeros_like(g); gk[b] = g[b]
+        _, it, _, hist = orc.cg(theta, dims, cfg.C, XS, gk, lam, 500, sigma=sigma, blockdiag=True, history=True)
+        own.append(it)
+    own_sorted = sorted(own)
+    assert len(set(own)) == 3                  # the three blocks finish at different iterations
+    _, it_all, _ = orc.cg(theta, dims, cfg.C, XS, g, lam, 500, sigma=sigma, blockdiag=True)
+    assert it_all == own_sorted[-1]
+    for r, expect in ((100.0, own_sorted[2]), (67.0, own_sorted[2]), (66.0, own_sorted[1]), (34.0, own_sorted[1]),
+                      (33.0, own_sorted[0]), (1.0, own_sorted[0])):
+        d, it, res = orc.cg(theta, dims, cfg.C, XS, g, lam, 500, sigma=sigma, blockdiag=True, cg_min=0, r_percent=r)
+        assert it == expect, (r, it, expect)
+    # cg_min delays the joint stop but not a block's own stop
+    cg_min = own_sorted[0] + 1
+    assert cg_min < own_sorted[1]
+    d, it, res, hist = orc.cg(theta, dims, cfg.C, XS, g, lam, 500, sigma=sigma, blockdiag=True, cg_min=cg_min,
+                              r_percent=1.0, history=True)
+    assert it == cg_min
+    first = own.index(own_sorted[0])
+    np.testing.assert_array_equal(hist[-1][blocks[first]], hist[own_sorted[0] - 1][blocks[first]])   # frozen since
+    # blocks cut short equal their own iterates at that count
+    for k, b in enumerate(blocks):
+        gk = np.zeros_like(g); gk[b] = g[b]
+        dk, _, _ = orc.cg(theta, dims, cfg.C, XS, gk, lam, min(cg_min, own[k]), sigma=0.0, blockdiag=True)
+        np.testing.assert_allclose(d[b], dk[b], rtol=1e-12, atol=1e-15)
+    # the single-system mode ignores the rule
+    d1, it1, _ = orc.cg(theta, dims, cfg.C, XS, g, lam, 50, sigma=0.0, blockdiag=False, r_percent=1.0)
+    assert it1 == 50
+
+
 # ------------------------------------------------------------------ outer Newton iteration
 
 def test_direction_combination_minimises_the_two_variable_model():
