@@ -133,6 +133,17 @@ int dn_cg(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter
           float* d, int* iters_host, double* resnorm_host);
 
 /*
+ * dn_cg on the per-layer systems (DN_BLOCKDIAG) with the early termination of Section 4.4: besides each
+ * block's own test and max_iter, ALL blocks stop after the first iteration k >= cg_min at which the number
+ * of blocks that have met their own test is >= r_percent/100 of the number of blocks (0 < r_percent <= 100;
+ * cg_min >= 0).  On one GPU the blocks advance in lock-step, so "every partition has run cg_min iterations"
+ * is k >= cg_min; the rule then only cuts iterations, it saves no waiting.  Outputs as dn_cg with
+ * resnorm_host[0..L-1].  The host looks at the blocks' state after every iteration (one synchronisation each).
+ */
+int dn_cg_sync(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter, int cg_min,
+               double r_percent, float* d, int* iters_host, double* resnorm_host);
+
+/*
  * One iteration of the subsampled Newton method (Section 4.5, the algorithm that summarises the
  * procedure, for one partition that owns every variable):
  *   1. g = grad f(theta) and f(theta) on all l rows;
@@ -163,6 +174,8 @@ typedef struct dn_newton_params {
     int mode;           /* DN_FULL or DN_BLOCKDIAG: matrix of the CG systems */
     int combine;        /* nonzero: step 4 */
     int max_trials;     /* >= 1 */
+    int cg_min;         /* with mode DN_BLOCKDIAG and r_percent > 0: early termination as in dn_cg_sync */
+    double r_percent;   /* <= 0: every block runs to its own test */
 } dn_newton_params;
 
 typedef struct dn_newton_stats {

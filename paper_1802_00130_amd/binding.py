@@ -26,7 +26,7 @@ class NewtonParams(ctypes.Structure):
     _fields_ = [("lam", ctypes.c_double), ("sigma", ctypes.c_double), ("eta", ctypes.c_double),
                 ("eps", ctypes.c_double), ("drop", ctypes.c_double), ("boost", ctypes.c_double),
                 ("cg_max", ctypes.c_int), ("mode", ctypes.c_int), ("combine", ctypes.c_int),
-                ("max_trials", ctypes.c_int)]
+                ("max_trials", ctypes.c_int), ("cg_min", ctypes.c_int), ("r_percent", ctypes.c_double)]
 
 
 class NewtonStats(ctypes.Structure):
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
         "dn_jacobian_read": (i, [vp, i, vp]),
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
+        "dn_cg_sync": (i, [vp, vp, d, d, i, i, d, vp, P(i), P(d)]),
         "dn_newton_step": (i, [vp, vp, vp, vp, i, vp, i, vp, P(NewtonParams), P(NewtonStats)]),
         "dn_set_stream_passes": (i, [vp, i]),
         "dn_set_spin_limit": (i, [vp, ctypes.c_uint]),
@@ -96,7 +97,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_cg_sync", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
     "dn_profile_enable",
     "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
@@ -249,17 +250,28 @@ def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int
     return iters.value, [res[k] for k in range(nres)]
 
 
+def dn_cg_sync(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int, cg_min: int,
+               r_percent: float, d: torch.Tensor) -> Tuple[int, list]:
+    """Per-layer CG with the joint early termination of Section 4.4; returns (iterations, residual norms)."""
+    iters = ctypes.c_int()
+    res = (ctypes.c_double * ctx.L)()
+    rc = ctx._lib.dn_cg_sync(ctx._h, _dev_f32(g, "g", ctx.n), float(lam), float(sigma), int(max_iter), int(cg_min),
+                             float(r_percent), _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
+    ctx._check(rc, "dn_cg_sync")
+    return iters.value, [res[k] for k in range(ctx.L)]
+
+
 def dn_newton_step(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor, S: torch.Tensor,
                    d_prev: torch.Tensor, lam: float, cg_max: int, sigma: float = 1e-3, eta: float = 1e-4,
                    eps: float = 1e-5, drop: float = 2.0 / 3.0, boost: float = 1.5, mode: int = DN_FULL,
-                   combine: bool = True, max_trials: int = 30) -> dict:
+                   combine: bool = True, max_trials: int = 30, cg_min: int = 0, r_percent: float = 0.0) -> dict:
     """One outer Newton iteration (Section 4.5): theta and d_prev are updated in place; returns the
     statistics of the step and the next lambda under key "lam"."""
     if not (S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()):
         raise TypeError("S: need a contiguous int32 device tensor")
     l = X.shape[0]
     prm = NewtonParams(float(lam), float(sigma), float(eta), float(eps), float(drop), float(boost), int(cg_max),
-                       int(mode), int(bool(combine)), int(max_trials))
+                       int(mode), int(bool(combine)), int(max_trials), int(cg_min), float(r_percent))
     st = NewtonStats()
     rc = ctx._lib.dn_newton_step(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
                                  _dev_f32(Y, "Y", l * ctx.dims[-1]), l, S.data_ptr(), S.numel(),

@@ -1002,12 +1002,10 @@ int dn_gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
     return gn_matvec(c, v, out, mode);
 }
 
-int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, float* d, int* iters_host,
-          double* resnorm_host) {
-    if (!c || !g || !d || !iters_host || !resnorm_host || bad_mode(mode) || max_iter < 1 || !(lambda >= 0.0) ||
-        !(sigma >= 0.0))
-        return DN_EINVAL;
-    if (!c->bound || !c->prepped) return DN_ESTATE;
+namespace {
+// CG of dn_cg / dn_cg_sync; r_percent <= 0 switches the joint termination of Section 4.4 off
+int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, int cg_min, double r_percent,
+           float* d, int* iters_host, double* resnorm_host) {
     CgSegs sg;
     build_segs(c, mode, sg);
     const int grid = sg.cb[sg.nseg];
@@ -1035,6 +1033,12 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
             if (s.active[k]) return true;
         return false;
     };
+    const bool joint = r_percent > 0.0;
+    auto joint_stop = [&](const CgState& s, int k) {
+        int finished = 0;
+        for (int b = 0; b < sg.nseg; ++b) finished += s.active[b] ? 0 : 1;
+        return k >= cg_min && (double)finished >= r_percent / 100.0 * (double)sg.nseg;
+    };
     int iters = 0;
     bool active = any_active(hst);
     while (iters < max_iter && active) {
@@ -1060,6 +1064,7 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
             DN_HIP(c, hipMemcpyAsync(&hst, nxt, sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
             DN_HIP(c, hipStreamSynchronize(c->stream));
             active = any_active(hst);
+            if (joint && joint_stop(hst, iters)) break;
         }
     }
     DN_HIP(c, hipMemcpyAsync(&hst, st + (iters & 1), sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
@@ -1068,6 +1073,25 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
     for (int k = 0; k < sg.nseg; ++k) resnorm_host[k] = std::sqrt(hst.rho[k]);
     return team_status(c);
 }
+}  // namespace
+
+int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, float* d, int* iters_host,
+          double* resnorm_host) {
+    if (!c || !g || !d || !iters_host || !resnorm_host || bad_mode(mode) || max_iter < 1 || !(lambda >= 0.0) ||
+        !(sigma >= 0.0))
+        return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    return cg_run(c, g, lambda, sigma, max_iter, mode, 0, 0.0, d, iters_host, resnorm_host);
+}
+
+int dn_cg_sync(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int cg_min, double r_percent,
+               float* d, int* iters_host, double* resnorm_host) {
+    if (!c || !g || !d || !iters_host || !resnorm_host || max_iter < 1 || cg_min < 0 || !(lambda >= 0.0) ||
+        !(sigma >= 0.0) || !(r_percent > 0.0 && r_percent <= 100.0))
+        return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    return cg_run(c, g, lambda, sigma, max_iter, DN_BLOCKDIAG, cg_min, r_percent, d, iters_host, resnorm_host);
+}
 
 int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int l, const int* S, int s, float* d_prev,
                    dn_newton_params* prm, dn_newton_stats* st) {
@@ -1075,7 +1099,7 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
         return DN_EINVAL;
     if (bad_mode(prm->mode) || prm->cg_max < 1 || prm->max_trials < 1 || !(prm->lambda >= 0.0) ||
         !(prm->sigma >= 0.0) || !(prm->eta > 0.0 && prm->eta < 1.0) || !(prm->drop > 0.0 && prm->drop <= 1.0) ||
-        !(prm->boost >= 1.0))
+        !(prm->boost >= 1.0) || prm->cg_min < 0 || !(prm->r_percent <= 100.0))
         return DN_EINVAL;
     if (!c->bound) return DN_ESTATE;
     std::memset(st, 0, sizeof(*st));
@@ -1097,7 +1121,9 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
     rc = dn_jacobian_prep(c, theta, X, l, S, s);
     if (rc != DN_OK) return rc;
     double resn[DN_MAX_LAYERS];
-    rc = dn_cg(c, g, prm->lambda, prm->sigma, prm->cg_max, prm->mode, d, &st->cg_iters, resn);
+    const bool joint = prm->mode == DN_BLOCKDIAG && prm->r_percent > 0.0;
+    rc = cg_run(c, g, prm->lambda, prm->sigma, prm->cg_max, prm->mode, joint ? prm->cg_min : 0,
+                joint ? prm->r_percent : 0.0, d, &st->cg_iters, resn);
     if (rc != DN_OK) return rc;
 
     // 4: inner products with the whole G^S

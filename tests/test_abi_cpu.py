@@ -75,13 +75,16 @@ def test_call_order_and_argument_errors(lib):
     assert lib.dn_gn_matvec(h, fake, fake, 5) == -1
     assert lib.dn_cg(h, fake, 1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
     assert lib.dn_cg(h, fake, -1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 0, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 0, 0.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, -1, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
     assert lib.dn_jacobian_read(h, 2, fake) == -1
     assert lib.dn_jacobian_read(h, 1, fake) == -3
-    prm = binding.NewtonParams(1.0, 1e-3, 1e-4, 1e-5, 2.0 / 3.0, 1.5, 10, 0, 1, 30)
+    prm = binding.NewtonParams(1.0, 1e-3, 1e-4, 1e-5, 2.0 / 3.0, 1.5, 10, 0, 1, 30, 0, 0.0)
     st = binding.NewtonStats()
     args = (h, fake, fake, fake, 10, fake, 5, fake)
     for field, bad in (("eta", 0.0), ("eta", 1.0), ("drop", 0.0), ("boost", 0.5), ("cg_max", 0), ("mode", 7),
-                       ("max_trials", 0), ("lam", -1.0)):
+                       ("max_trials", 0), ("lam", -1.0), ("cg_min", -1), ("r_percent", 101.0)):
         good = getattr(prm, field)
         setattr(prm, field, bad)
         assert lib.dn_newton_step(*args, ctypes.byref(prm), ctypes.byref(st)) == -1, field
