@@ -35,7 +35,7 @@ typedef struct dn_ctx dn_ctx;
 
 enum {
     DN_OK = 0,
-    DN_EINVAL = -1,   /* null pointer, non-positive size, s > s_max, l > l_max, bad mode or layer */
+    DN_EINVAL = -1,   /* null pointer, non-positive size, s > s_max, bad mode, layer or parameter */
     DN_ENOSPC = -2,   /* workspace given to dn_bind is smaller than dn_workspace_bytes() */
     DN_ESTATE = -3,   /* call needs a bound workspace / a prior dn_jacobian_prep and there is none */
     DN_EHIP = -4,     /* a HIP runtime call failed; dn_last_hip_error() gives the HIP code */
@@ -54,9 +54,11 @@ const char* dn_strerror(int code);
 
 /*
  * Create a context for the network dims[0..L] (L >= 1 weight layers, every entry >= 1) with
- * regularisation parameter C > 0 of the objective (Section 2.1).  l_max / s_max bound the
- * number of rows later passed to dn_forward / dn_grad and the subsample size passed to
- * dn_jacobian_prep; they size the workspace.  Host-only: touches no device.
+ * regularisation parameter C > 0 of the objective (Section 2.1).  l_max is the number of rows whose
+ * activations the workspace holds at a time: dn_forward / dn_grad take any number of rows l and send
+ * them through in ceil(l / l_max) chunks that reuse the same buffers (the mini-batch pipeline of
+ * Section 6.1: memory / R for R chunks; the results are the same sums).  s_max bounds the subsample
+ * size passed to dn_jacobian_prep.  Both size the workspace.  Host-only: touches no device.
  */
 int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_max);
 void dn_destroy(dn_ctx* ctx);
@@ -78,7 +80,8 @@ int dn_bind(dn_ctx* ctx, void* d_workspace, size_t bytes, void* hip_stream);
 /*
  * Objective value (Section 2.1):
  *   f = theta^T theta / (2C) + (1/l) sum_i || z^{L,i} - y^i ||^2 .
- * l <= l_max rows of X and Y are used.  *f_host receives f (fp64 accumulation of fp32 terms).
+ * All l rows of X and Y are used (in chunks of l_max rows).  *f_host receives f (fp64 accumulation of
+ * fp32 terms).
  * If ZL is non-null it receives the network outputs, [l x n_L] dense.
  */
 int dn_forward(dn_ctx* ctx, const float* theta, const float* X, const float* Y, int l,

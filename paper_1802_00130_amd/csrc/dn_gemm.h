@@ -65,6 +65,7 @@ struct GemmProblem {
     int tile_begin;      // first tile id of this problem within one K-slice of the group
     int b_ones_col;      // 1: column N-1 of op(B) is a virtual column of ones (not read from memory);
                          //    only for a row-contiguous B
+    int accumulate;      // 1: the result is added to what C (of the same K-slice) already holds
 };
 
 struct GemmGroup {
@@ -637,7 +638,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 
     // ---- epilogue: lane holds column n = .. + r and rows 8*(e/4) + 4*h + e%4 of each 32x32 block ----
     float* __restrict__ Cb = P.C + (long long)split * P.split_stride;
-    const bool plain = !P.sigmoid && !P.aux && !P.add;      // uniform: keep the common case branch-free
+    const bool plain = !P.sigmoid && !P.aux && !P.add && !P.accumulate;      // uniform: keep the common case branch-free
     const float alpha = P.alpha;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -664,6 +665,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
                         x *= z * (1.0f - z);
                     }
                     if (P.add) x += P.add[(long long)m * P.ldadd + n];
+                    if (P.accumulate) x += Cb[(long long)m * P.ldc + n];
                     Cb[(long long)m * P.ldc + n] = x;
                 }
             }

@@ -135,10 +135,12 @@ __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict
 // ---------------------------------------------------------------------------------------------
 // Loss partial sums: sum (z - y)^2 in fp64; optionally writes the back-propagation seed
 // 2 (z^L - y)  (Section 3.4) and a dense copy of z^L.
+// accumulate != 0: the partial sums are added to what an earlier chunk of the samples left there.
 __global__ __launch_bounds__(256) void loss_delta_kernel(const float* __restrict__ ZL, long long ldz,
                                                          const float* __restrict__ Y, int l, int nL,
                                                          float* __restrict__ delta, long long ldd,
-                                                         float* __restrict__ zl_out, double* __restrict__ partials) {
+                                                         float* __restrict__ zl_out, double* __restrict__ partials,
+                                                         int accumulate) {
     __shared__ double red[4];
     const long long total = (long long)l * nL;
     double acc = 0.0;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(256) void loss_delta_kernel(const float* __restrict
         if (zl_out) zl_out[e] = z;
     }
     acc = block_sum_d(acc, red);
-    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+    if (threadIdx.x == 0) partials[blockIdx.x] = accumulate ? partials[blockIdx.x] + acc : acc;
 }
 
 __global__ __launch_bounds__(256) void sumsq_kernel(const float* __restrict__ x, long long n,

@@ -416,26 +416,31 @@ int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0
 }
 
 // objective from Z^L of all rows; optionally writes the gradient seed 2(z^L - y)
-int objective(dn_ctx* c, const float* theta, const float* Y, int l, float* delta, long long ldd, float* zl_out,
-              double* f_host) {
+// Loss terms of the `rows` samples whose outputs are in Z^L of the workspace (one chunk of the l samples);
+// optionally the gradient seed 2(z^L - y) and a dense copy of z^L.  first: this is the first chunk (the
+// partial sums start from zero).  last && f_host: add the regularisation term and return f.
+int objective(dn_ctx* c, const float* theta, const float* Y, int rows, int l, bool first, bool last, float* delta,
+              long long ldd, float* zl_out, double* f_host) {
     const int L = c->L;
-    const int nb_loss = std::min(DN_MAX_PARTIALS, grid_for((long long)l * c->dims[L]));
+    // the grid of the first (largest) chunk defines how many partial sums there are
+    const int nb_all = std::min(DN_MAX_PARTIALS, grid_for((long long)std::min(l, c->l_max) * c->dims[L]));
+    const int nb_loss = std::min(nb_all, grid_for((long long)rows * c->dims[L]));
     const int nb_reg = std::min(DN_MAX_PARTIALS, grid_for(c->n));
     ProfScope ps(c, KC_LOSS);
     DN_HIP(c, ps.err);
     hipLaunchKernelGGL(loss_delta_kernel, dim3(nb_loss), dim3(256), 0, c->stream, c->fptr(c->o_Zall[L]), c->ld[L], Y,
-                       l, c->dims[L], delta, ldd, zl_out, c->dptr(c->o_part[0]));
+                       rows, c->dims[L], delta, ldd, zl_out, c->dptr(c->o_part[0]), first ? 0 : 1);
     DN_HIP(c, hipGetLastError());
-    if (f_host) {
+    if (f_host && last) {
         hipLaunchKernelGGL(sumsq_kernel, dim3(nb_reg), dim3(256), 0, c->stream, theta, c->n, c->dptr(c->o_part[1]));
         DN_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(objective_finalize_kernel, dim3(1), dim3(256), 0, c->stream, c->dptr(c->o_part[0]),
-                           nb_loss, c->dptr(c->o_part[1]), nb_reg, 1.0 / (2.0 * c->C), 1.0 / (double)l,
+                           nb_all, c->dptr(c->o_part[1]), nb_reg, 1.0 / (2.0 * c->C), 1.0 / (double)l,
                            c->dptr(c->o_f));
         DN_HIP(c, hipGetLastError());
     }
     DN_HIP(c, ps.end());
-    if (f_host) {
+    if (f_host && last) {
         DN_HIP(c, hipMemcpyAsync(f_host, c->dptr(c->o_f), sizeof(double), hipMemcpyDeviceToHost, c->stream));
         DN_HIP(c, hipStreamSynchronize(c->stream));
     }
@@ -852,32 +857,36 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
 }
 
 int dn_forward(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, double* f_host, float* ZL) {
-    if (!c || !theta || !X || !Y || !f_host || l < 1 || l > c->l_max) return DN_EINVAL;
+    if (!c || !theta || !X || !Y || !f_host || l < 1) return DN_EINVAL;
     if (!c->bound) return DN_ESTATE;
-    int rc = forward_layers(c, theta, X, c->dims[0], l, c->o_Zall, c->L);
-    if (rc != DN_OK) return rc;
-    return objective(c, theta, Y, l, nullptr, 0, ZL, f_host);
+    const int L = c->L, n0 = c->dims[0], nL = c->dims[L];
+    // the samples go through in chunks of at most l_max rows that reuse the same activation buffers
+    for (int r0 = 0; r0 < l; r0 += c->l_max) {
+        const int rows = std::min(c->l_max, l - r0);
+        int rc = forward_layers(c, theta, X + (long long)r0 * n0, n0, rows, c->o_Zall, L);
+        if (rc != DN_OK) return rc;
+        rc = objective(c, theta, Y + (long long)r0 * nL, rows, l, r0 == 0, r0 + rows == l, nullptr, 0,
+                       ZL ? ZL + (long long)r0 * nL : nullptr, f_host);
+        if (rc != DN_OK) return rc;
+    }
+    return DN_OK;
 }
 
 int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, float* g, double* f_host) {
-    if (!c || !theta || !X || !Y || !g || l < 1 || l > c->l_max) return DN_EINVAL;
+    if (!c || !theta || !X || !Y || !g || l < 1) return DN_EINVAL;
     if (!c->bound) return DN_ESTATE;
-    const int L = c->L;
-    int rc = forward_layers(c, theta, X, c->dims[0], l, c->o_Zall, L);
-    if (rc != DN_OK) return rc;
-    // seed 2 (z^L - y) into D[0]
-    int cur = 0;
-    rc = objective(c, theta, Y, l, c->fptr(c->o_D[cur]), c->ld[L], nullptr, f_host);
-    if (rc != DN_OK) return rc;
+    const int L = c->L, n0 = c->dims[0], nL = c->dims[L];
     if (L >= 2) {
-        rc = transpose_weights(c, theta, 2, L);
+        int rc = transpose_weights(c, theta, 2, L);
         if (rc != DN_OK) return rc;
     }
+    // plan of the sums over samples, from the size of a full chunk; every chunk adds into the same slices
+    const int rows_full = std::min(l, c->l_max);
     TnPlan plans[DN_MAX_LAYERS + 1];
     // partial buffers of different layers must not overlap: give each layer its own range
     long long tn_off = 0;
     for (int m = 1; m <= L; ++m) {
-        plans[m] = plan_tn(c, l, false, m);
+        plans[m] = plan_tn(c, rows_full, false, m);
         plans[m].offset[m] = tn_off;
         tn_off += round_up(plans[m].floats[m], 64);
     }
@@ -886,47 +895,59 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
         tn_off = 0;
         for (int m = 1; m <= L; ++m) {
             plans[m].splits = 1;
-            plans[m].k_per_split = (int)round_up(l, kBKmax);
+            plans[m].k_per_split = (int)round_up(rows_full, kBKmax);
             plans[m].floats[m] = (long long)c->dims[m] * c->ldw[m];
             plans[m].offset[m] = tn_off;
             tn_off += round_up(plans[m].floats[m], 64);
         }
         if (tn_off > c->tn_floats) return DN_ENOSPC;
     }
-    for (int m = L; m >= 1; --m) {
-        const float* delta = c->fptr(c->o_D[cur]);
-        const float* zprev = (m == 1) ? X : c->fptr(c->o_Zall[m - 1]);
-        const long long ldprev = (m == 1) ? c->dims[0] : c->ld[m - 1];
-        {
-            // sum over samples: delta^m^T [z^{m-1}, 1]
-            GemmGroup g1;
-            g1.nprob = 1;
-            GemmProblem& p = g1.p[0];
-            p = mk_problem(delta, c->ld[m], zprev, ldprev, c->fptr(c->o_tn) + plans[m].offset[m], c->ldw[m],
-                           c->dims[m], c->dims[m - 1] + 1, l);
-            p.b_ones_col = 1;
-            p.split_stride = (long long)c->dims[m] * c->ldw[m];
-            ProfScope ps(c, KC_GEMM_TN_GRAD);
-            DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_GRAD>(g1, plans[m].tile, plans[m].splits, c->stream)));
-            DN_HIP(c, ps.end());
-        }
-        if (m > 1) {
-            // delta^{m-1} = (delta^m (W^m)^T) * z^{m-1} (1 - z^{m-1})
-            GemmGroup g2;
-            g2.nprob = 1;
-            GemmProblem& p = g2.p[0];
-            p = mk_problem(delta, c->ld[m], c->fptr(c->o_WT) + c->woff[m], c->dims[m], c->fptr(c->o_D[cur ^ 1]),
-                           c->ld[m - 1], l, c->dims[m - 1], c->dims[m]);
-            p.aux = zprev;
-            p.ldaux = ldprev;
-            p.auxdiv = 1;
-            const int tile = pick_tile(g2, true);
-            ProfScope ps(c, KC_GEMM_BACK);
-            DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
-            DN_HIP(c, ps.end());
-            cur ^= 1;
+    for (int r0 = 0; r0 < l; r0 += c->l_max) {
+        const int rows = std::min(c->l_max, l - r0);
+        const float* Xc = X + (long long)r0 * n0;
+        int rc = forward_layers(c, theta, Xc, n0, rows, c->o_Zall, L);
+        if (rc != DN_OK) return rc;
+        // seed 2 (z^L - y) into D[0]
+        int cur = 0;
+        rc = objective(c, theta, Y + (long long)r0 * nL, rows, l, r0 == 0, r0 + rows == l, c->fptr(c->o_D[cur]),
+                       c->ld[L], nullptr, f_host);
+        if (rc != DN_OK) return rc;
+        for (int m = L; m >= 1; --m) {
+            const float* delta = c->fptr(c->o_D[cur]);
+            const float* zprev = (m == 1) ? Xc : c->fptr(c->o_Zall[m - 1]);
+            const long long ldprev = (m == 1) ? n0 : c->ld[m - 1];
+            {
+                // sum over samples: delta^m^T [z^{m-1}, 1]
+                GemmGroup g1;
+                g1.nprob = 1;
+                GemmProblem& p = g1.p[0];
+                p = mk_problem(delta, c->ld[m], zprev, ldprev, c->fptr(c->o_tn) + plans[m].offset[m], c->ldw[m],
+                               c->dims[m], c->dims[m - 1] + 1, rows);
+                p.b_ones_col = 1;
+                p.split_stride = (long long)c->dims[m] * c->ldw[m];
+                p.accumulate = r0 > 0 ? 1 : 0;
+                ProfScope ps(c, KC_GEMM_TN_GRAD);
+                DN_HIP(c, ps.err);
+                DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_GRAD>(g1, plans[m].tile, plans[m].splits, c->stream)));
+                DN_HIP(c, ps.end());
+            }
+            if (m > 1) {
+                // delta^{m-1} = (delta^m (W^m)^T) * z^{m-1} (1 - z^{m-1})
+                GemmGroup g2;
+                g2.nprob = 1;
+                GemmProblem& p = g2.p[0];
+                p = mk_problem(delta, c->ld[m], c->fptr(c->o_WT) + c->woff[m], c->dims[m], c->fptr(c->o_D[cur ^ 1]),
+                               c->ld[m - 1], rows, c->dims[m - 1], c->dims[m]);
+                p.aux = zprev;
+                p.ldaux = ldprev;
+                p.auxdiv = 1;
+                const int tile = pick_tile(g2, true);
+                ProfScope ps(c, KC_GEMM_BACK);
+                DN_HIP(c, ps.err);
+                DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
+                DN_HIP(c, ps.end());
+                cur ^= 1;
+            }
         }
     }
     return tn_reduce(c, plans, true, theta, g, 1.0 / (double)l);
@@ -1095,7 +1116,7 @@ int dn_cg_sync(dn_ctx* c, const float* g, double lambda, double sigma, int max_i
 
 int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int l, const int* S, int s, float* d_prev,
                    dn_newton_params* prm, dn_newton_stats* st) {
-    if (!c || !theta || !X || !Y || !S || !d_prev || !prm || !st || l < 1 || l > c->l_max || s < 1 || s > c->s_max)
+    if (!c || !theta || !X || !Y || !S || !d_prev || !prm || !st || l < 1 || s < 1 || s > c->s_max)
         return DN_EINVAL;
     if (bad_mode(prm->mode) || prm->cg_max < 1 || prm->max_trials < 1 || !(prm->lambda >= 0.0) ||
         !(prm->sigma >= 0.0) || !(prm->eta > 0.0 && prm->eta < 1.0) || !(prm->drop > 0.0 && prm->drop <= 1.0) ||

@@ -68,7 +68,7 @@ def test_call_order_and_argument_errors(lib):
     assert lib.dn_bind(h, fake, 16, None) == -2                                      # too small
     assert lib.dn_bind(h, fake, lib.dn_workspace_bytes(h), None) == 0
     assert lib.dn_forward(h, None, fake, fake, 10, ctypes.byref(f), None) == -1
-    assert lib.dn_forward(h, fake, fake, fake, 101, ctypes.byref(f), None) == -1     # l > l_max
+    assert lib.dn_forward(h, fake, fake, fake, 0, ctypes.byref(f), None) == -1
     assert lib.dn_grad(h, fake, fake, fake, 0, fake, None) == -1
     assert lib.dn_jacobian_prep(h, fake, fake, 100, fake, 11) == -1                  # s > s_max
     assert lib.dn_gn_matvec(h, fake, fake, 0) == -3                                  # no Jacobian prepared

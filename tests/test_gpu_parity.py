@@ -164,3 +164,34 @@ def test_zero_gradient_and_error_paths(wl):
         dn.dn_gn_matvec(wl.ctx, d, wl.empty(), 7)
     with pytest.raises(dn.DnError):
         dn.dn_cg(wl.ctx, d, 1.0, 0.0, 0, dn.DN_FULL, wl.empty())
+
+
+@pytest.mark.parametrize("l_max", [64, 100, 333, 1000])
+def test_chunked_objective_and_gradient(l_max):
+    """Section 6.1 pipeline: the samples go through in chunks of l_max rows that reuse the activation buffers;
+    f and the gradient must be the same sums (chunk sizes that divide l, that leave a ragged last chunk, that
+    equal l, and that exceed l)."""
+    cfg = dn_inputs.custom((70, 133, 45, 19), l=333, s=131, C=10.0, seed=16)
+    X, Y = dn_inputs.make_X(cfg), dn_inputs.make_Y(cfg)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.3)
+    dev = "cuda:0"
+    dX, dY, dth = (torch.from_numpy(a).to(dev) for a in (X, Y, theta))
+    ctx = dn.Context(cfg.dims, cfg.C, l_max, cfg.s)
+    g = torch.empty(ctx.n, dtype=torch.float32, device=dev)
+    ZL = torch.empty(cfg.l, cfg.dims[-1], dtype=torch.float32, device=dev)
+    th64, X64, Y64 = theta.astype(np.float64), X.astype(np.float64), Y.astype(np.float64)
+    g_ref, f_ref = orc.grad(th64, cfg.dims, cfg.C, X64, Y64)
+    f = dn.dn_forward(ctx, dth, dX, dY, ZL)
+    assert abs(f - f_ref) <= TOL * abs(f_ref)
+    assert rel_l2(ZL.cpu().numpy(), orc.forward(th64, cfg.dims, X64)[-1]) <= TOL
+    f2 = dn.dn_grad(ctx, dth, dX, dY, g)
+    assert abs(f2 - f_ref) <= TOL * abs(f_ref)
+    assert rel_l2(g.cpu().numpy(), g_ref) <= TOL
+    # a Newton step whose f and gradient are chunked gives the same step as the oracle
+    S = torch.from_numpy(dn_inputs.make_subset(cfg)).to(dev)
+    d_prev = torch.zeros_like(g)
+    th_new = dth.clone()
+    out = dn.dn_newton_step(ctx, th_new, dX, dY, S, d_prev, 1.0, 6, sigma=0.0)
+    ref = orc.newton_step(th64, cfg.dims, cfg.C, X64, Y64, dn_inputs.make_subset(cfg), np.zeros(ctx.n), 1.0, 6, sigma=0.0)
+    assert out["alpha"] == ref["alpha"] and abs(out["f_new"] - ref["f_new"]) <= TOL * abs(ref["f_new"])
+    ctx.close()
