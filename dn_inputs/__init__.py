@@ -132,21 +132,38 @@ def make_Y(cfg: Config, rows: int | None = None) -> np.ndarray:
     return Y
 
 
-def make_theta(cfg: Config, bias_scale: float = 0.0) -> np.ndarray:
+def make_theta(cfg: Config, bias_scale: float = 0.0, init: str = "xavier") -> np.ndarray:
     """Initial parameters, fp32, theta layout.
 
-    Weights: Xavier-uniform U(-a, a), a = sqrt(6 / (n_{m-1} + n_m)).
+    init = "xavier": weights Xavier-uniform U(-a, a), a = sqrt(6 / (n_{m-1} + n_m)).
+    init = "sparse": the sparse initialisation of Section 6.2 with the count of Section 8.1: of the n_{m-1}
+        weights into each neuron of layer m, ceil(sqrt(n_{m-1})) chosen at random are N(0, 1), the rest zero.
+    init = "dense": the dense initialisation of Section 8.3: N(0, 0.1^2) in the first layer, N(0, 0.001^2)
+        in the output layer, N(0, 0.05^2) in the other layers.
     Biases: zero, or U(-bias_scale, bias_scale) when bias_scale > 0 so that
     tests exercise the bias paths.
     """
+    if init not in ("xavier", "sparse", "dense"):
+        raise ValueError(f"unknown init {init!r}")
     g = _rng(cfg.seed, _ST_THETA)
     gb = _rng(cfg.seed, _ST_BIAS)
     theta = np.zeros(cfg.n_params, dtype=np.float32)
+    L = len(cfg.dims) - 1
     for m, (w, b) in enumerate(layer_offsets(cfg.dims), start=1):
         fan_in, fan_out = cfg.dims[m - 1], cfg.dims[m]
-        a = math.sqrt(6.0 / (fan_in + fan_out))
-        u = g.random(fan_in * fan_out, dtype=np.float32)
-        theta[w:w + fan_in * fan_out] = (2.0 * u - 1.0) * np.float32(a)
+        if init == "xavier":
+            a = math.sqrt(6.0 / (fan_in + fan_out))
+            u = g.random(fan_in * fan_out, dtype=np.float32)
+            theta[w:w + fan_in * fan_out] = (2.0 * u - 1.0) * np.float32(a)
+        elif init == "sparse":
+            k = math.isqrt(fan_in - 1) + 1 if fan_in > 0 else 0          # ceil(sqrt(fan_in))
+            A = theta[w:w + fan_in * fan_out].reshape(fan_out, fan_in)     # row j: the weights into neuron j
+            for j in range(fan_out):
+                cols = g.permutation(fan_in)[:k]
+                A[j, cols] = g.standard_normal(k, dtype=np.float32)
+        else:
+            sd = 0.1 if m == 1 else (0.001 if m == L else 0.05)
+            theta[w:w + fan_in * fan_out] = g.standard_normal(fan_in * fan_out, dtype=np.float32) * np.float32(sd)
         if bias_scale > 0.0:
             ub = gb.random(fan_out, dtype=np.float32)
             theta[b:b + fan_out] = (2.0 * ub - 1.0) * np.float32(bias_scale)

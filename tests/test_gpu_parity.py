@@ -195,3 +195,23 @@ def test_chunked_objective_and_gradient(l_max):
     ref = orc.newton_step(th64, cfg.dims, cfg.C, X64, Y64, dn_inputs.make_subset(cfg), np.zeros(ctx.n), 1.0, 6, sigma=0.0)
     assert out["alpha"] == ref["alpha"] and abs(out["f_new"] - ref["f_new"]) <= TOL * abs(ref["f_new"])
     ctx.close()
+
+
+@pytest.mark.parametrize("init", ["sparse", "dense"])
+def test_paper_initialisations(init):
+    """Gradient and both products at the paper's own initial points (Section 6.2 sparse, Section 8.3 dense)."""
+    cfg = dn_inputs.custom((200, 300, 260, 10), l=600, s=200, C=600.0, seed=17)
+    w = Workload(cfg)
+    w.theta = dn_inputs.make_theta(cfg, init=init)
+    w.dtheta = torch.from_numpy(w.theta).to("cuda:0")
+    g = w.empty()
+    f = dn.dn_grad(w.ctx, w.dtheta, w.dX, w.dY, g)
+    g_ref, f_ref = orc.grad(w.theta.astype(np.float64), cfg.dims, cfg.C, w.X.astype(np.float64), w.Y.astype(np.float64))
+    assert abs(f - f_ref) <= TOL * abs(f_ref) and rel_l2(g.cpu().numpy(), g_ref) <= TOL
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    v = dn_inputs.make_probe(cfg, 0)
+    out = w.empty()
+    for mode in (dn.DN_FULL, dn.DN_BLOCKDIAG):
+        dn.dn_gn_matvec(w.ctx, w.dev(v), out, mode)
+        assert rel_l2(out.cpu().numpy(), w.oracle_matvec(v, blockdiag=(mode == dn.DN_BLOCKDIAG))) <= TOL
+    w.ctx.close()

@@ -503,3 +503,16 @@ def test_input_generator_shapes_and_ranges():
     X4 = dn_inputs.make_X(c4)
     assert X4.min() >= -3.0 and X4.max() <= 3.0 and abs(float(X4.mean())) < 0.1
     assert [dn_inputs.config(i).n_params for i in range(1, 6)] == [676, 328810, 3578510, 12302100, 71222248]
+    # sparse initialisation: ceil(sqrt(n_{m-1})) non-zero weights into every neuron, zero biases
+    cs = dn_inputs.custom((50, 17, 10, 3), l=10, s=5)
+    ths = dn_inputs.make_theta(cs, init="sparse")
+    for m, (w, b) in enumerate(dn_inputs.layer_offsets(cs.dims), start=1):
+        A = ths[w:w + cs.dims[m - 1] * cs.dims[m]].reshape(cs.dims[m], cs.dims[m - 1])
+        assert np.all((A != 0).sum(axis=1) == math.ceil(math.sqrt(cs.dims[m - 1])))
+        assert np.all(ths[b:b + cs.dims[m]] == 0)
+    assert [math.ceil(math.sqrt(k)) for k in (50, 17, 10)] == [8, 5, 4]
+    # dense initialisation: per-layer standard deviations 0.1 / 0.05 / 0.001
+    cd = dn_inputs.custom((400, 300, 200, 100), l=10, s=5)
+    thd = dn_inputs.make_theta(cd, init="dense")
+    sds = [thd[w:w + cd.dims[m] * cd.dims[m + 1]].std() for m, (w, _) in enumerate(dn_inputs.layer_offsets(cd.dims))]
+    np.testing.assert_allclose(sds, [0.1, 0.05, 0.001], rtol=0.02)
