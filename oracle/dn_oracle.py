@@ -17,6 +17,8 @@ What is computed, and from where in the paper:
                                                 Section 4.3 (subsampled Gauss-Newton
                                                 matrix), Section 3.1 (B for squared loss)
 * block-diagonal product, one block per layer   Section 4.1
+* the same for a general split structure        Section 3.1 (variable partitions, where the biases go),
+  (neuron groups per layer)                     Section 4.1
 * conjugate gradient on (G^S + lambda I) d = -g Section 2.2 / 4.3 linear system, Section 4.1
                                                 stopping rule
 * the stored blocks P^m_i = d z^{L,i} / d s^{m,i} by the backward recursion
@@ -201,9 +203,57 @@ def gn_matvec_blockdiag(theta, dims, C, XS, v):
     return out
 
 
+# --------------------------------------------------------------------------- variable partitions
+
+def group_bounds(n, groups):
+    """Boundaries of `groups` contiguous, as-equal-as-possible neuron groups of a layer with n neurons."""
+    return [(k * n) // groups for k in range(groups + 1)]
+
+
+def partition_index_sets(dims, split):
+    """Index sets (into a theta-layout vector) of the variable partitions of Section 3.1.
+
+    split[m] = number of neuron groups of layer m (m = 0..L).  The weights between group a of layer m-1
+    and group b of layer m form one partition; the biases of group b of layer m go with the partition of
+    the FIRST group of layer m-1 (a = 0).  Order: layer by layer, a outer, b inner.
+    """
+    assert len(split) == len(dims)
+    sets = []
+    o = 0
+    for m in range(1, len(dims)):
+        nprev, ncur = dims[m - 1], dims[m]
+        ga = group_bounds(nprev, split[m - 1])
+        gb = group_bounds(ncur, split[m])
+        boff = o + nprev * ncur
+        for a in range(split[m - 1]):
+            for b in range(split[m]):
+                j = np.arange(gb[b], gb[b + 1])
+                t = np.arange(ga[a], ga[a + 1])
+                idx = (o + j[:, None] * nprev + t[None, :]).ravel()      # w^m_{tj} sits at j * n_{m-1} + t
+                if a == 0:
+                    idx = np.concatenate([idx, boff + j])
+                sets.append(idx)
+        o = boff + ncur
+    return sets
+
+
+def gn_matvec_partitioned(theta, dims, C, XS, v, split):
+    """Block-diagonal product for a general split structure (Section 4.1 with the partitions of
+    Section 3.1), taken literally: for each partition p, zero the rest of v, apply the whole product,
+    keep the entries of p."""
+    v = np.asarray(v, dtype=np.float64)
+    out = np.zeros_like(v)
+    for idx in partition_index_sets(dims, split):
+        vp = np.zeros_like(v)
+        vp[idx] = v[idx]
+        out[idx] = gn_matvec(theta, dims, C, XS, vp)[idx]
+    return out
+
+
 # --------------------------------------------------------------------------- CG
 
-def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history=False, cg_min=0, r_percent=None):
+def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history=False, cg_min=0, r_percent=None,
+       split=None):
     """Conjugate gradient on (G^S + lam I) d = -g  (Sections 2.2, 4.3).
 
     d_0 = 0, r_0 = -g, p_0 = r_0, no preconditioner.  After each step the recurrence
@@ -211,6 +261,9 @@ def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history
     blockdiag=True the L per-layer systems are solved independently, each block with
     its own step lengths and its own stopping test; a block that has met its test is
     left unchanged afterwards.
+
+    split (with blockdiag=True): the independent systems are those of the partitions of that split structure
+    (Section 3.1) instead of one per layer.
 
     r_percent (block-diagonal systems only, Section 4.4): the early termination that spares the blocks still
     running from holding up the others: all blocks stop after the first iteration k >= cg_min at which the
@@ -222,8 +275,14 @@ def cg(theta, dims, C, XS, g, lam, max_iter, sigma=0.0, blockdiag=False, history
     """
     g = np.asarray(g, dtype=np.float64)
     n = g.shape[0]
-    blocks = block_slices(dims) if blockdiag else [slice(0, n)]
-    product = gn_matvec_blockdiag if blockdiag else gn_matvec
+    if blockdiag and split is not None:
+        blocks = partition_index_sets(dims, split)
+
+        def product(th, dm, Cc, Xs, p):
+            return gn_matvec_partitioned(th, dm, Cc, Xs, p, split)
+    else:
+        blocks = block_slices(dims) if blockdiag else [slice(0, n)]
+        product = gn_matvec_blockdiag if blockdiag else gn_matvec
     d = np.zeros(n)
     r = -g.copy()
     p = r.copy()

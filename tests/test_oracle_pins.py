@@ -329,6 +329,65 @@ def test_cg_blockdiag_blocks_stop_independently():
         np.testing.assert_allclose(d[b], dk[b], rtol=1e-12, atol=1e-15)
 
 
+def test_variable_partitions_follow_the_papers_example():
+    # Section 3.1: a 150-200-30 network split 3-2-3 has 12 partitions; (A0, A1) holds a 50 x 100 block of W^1;
+    # the 200 biases of layer 1 are split 100 / 100 between the two partitions of the FIRST input group
+    dims, split = (150, 200, 30), (3, 2, 3)
+    sets = orc.partition_index_sets(dims, split)
+    assert len(sets) == 12
+    n = orc.num_params(dims)
+    allidx = np.concatenate(sets)
+    assert allidx.size == n and np.array_equal(np.sort(allidx), np.arange(n))      # a partition of the variables
+    sizes = [s.size for s in sets]
+    assert sizes[:6] == [50 * 100 + 100, 50 * 100 + 100, 50 * 100, 50 * 100, 50 * 100, 50 * 100]
+    assert sizes[6:] == [100 * 10 + 10] * 3 + [100 * 10] * 3
+    # element check with the index formula of Section 2.1: w^1_{tj} at j * 150 + t
+    A01 = set(sets[1].tolist())                     # (a = 0, b = 1): t in 0..49, j in 100..199
+    assert (100 * 150 + 0) in A01 and (199 * 150 + 49) in A01 and (100 * 150 + 50) not in A01
+    assert (150 * 200 + 100) in A01 and (150 * 200 + 99) not in A01              # bias b^1_100
+    # one group everywhere = one partition per layer
+    for sl, idx in zip(orc.block_slices(dims), orc.partition_index_sets(dims, (1, 1, 1))):
+        assert np.array_equal(np.sort(idx), np.arange(sl.start, sl.stop))
+
+
+@pytest.mark.parametrize("dims,split", [((4, 3, 3, 2), (2, 1, 3, 1)), ((5, 4, 3), (3, 2, 2)), ((6, 4), (2, 3))])
+def test_partitioned_product_is_the_block_diagonal_of_dense_G(dims, split):
+    # catches: biases assigned to the wrong partition, cross-partition terms kept, wrong group boundaries
+    cfg, X, Y, theta, S = _tiny(dims, l=8, s=5)
+    XS = X[S]
+    G = tiny_ref.dense_gauss_newton(theta, dims, cfg.C, XS)
+    # membership map built here from the paper's description, not from the oracle's index sets
+    owner = np.empty(G.shape[0], dtype=np.int64)
+    o, pid = 0, 0
+    for m in range(1, len(dims)):
+        nprev, ncur = dims[m - 1], dims[m]
+        ga = [(k * nprev) // split[m - 1] for k in range(split[m - 1] + 1)]
+        gb = [(k * ncur) // split[m] for k in range(split[m] + 1)]
+        grp_prev = np.searchsorted(ga, np.arange(nprev), side="right") - 1
+        grp_cur = np.searchsorted(gb, np.arange(ncur), side="right") - 1
+        for j in range(ncur):
+            for t in range(nprev):
+                owner[o + j * nprev + t] = pid + grp_prev[t] * split[m] + grp_cur[j]
+            owner[o + nprev * ncur + j] = pid + 0 * split[m] + grp_cur[j]
+        o += nprev * ncur + ncur
+        pid += split[m - 1] * split[m]
+    Ghat = np.where(owner[:, None] == owner[None, :], G, 0.0)
+    rng = np.random.default_rng(3)
+    for _ in range(3):
+        v = rng.standard_normal(G.shape[0])
+        np.testing.assert_allclose(orc.gn_matvec_partitioned(theta, dims, cfg.C, XS, v, split), Ghat @ v,
+                                   rtol=2e-6, atol=1e-8)
+    # CG over the partitions solves the block-diagonal system
+    g, _ = orc.grad(theta, dims, cfg.C, X, Y)
+    d, it, res = orc.cg(theta, dims, cfg.C, XS, g, 0.2, 300, sigma=1e-12, blockdiag=True, split=split)
+    np.testing.assert_allclose(d, np.linalg.solve(Ghat + 0.2 * np.eye(G.shape[0]), -g), rtol=1e-6, atol=1e-9)
+    assert len(res) == sum(split[m - 1] * split[m] for m in range(1, len(dims)))
+    # with one group per layer it is the per-layer product
+    v = rng.standard_normal(G.shape[0])
+    np.testing.assert_allclose(orc.gn_matvec_partitioned(theta, dims, cfg.C, XS, v, (1,) * len(dims)),
+                               orc.gn_matvec_blockdiag(theta, dims, cfg.C, XS, v), rtol=1e-13, atol=1e-15)
+
+
 def test_cg_early_termination_across_blocks():
     # catches: the percentage applied to running instead of finished blocks, cg_min ignored, a finished block
     # still being updated, the rule leaking into the single-system mode
