@@ -46,7 +46,8 @@ enum {
 /* mode of dn_gn_matvec and dn_cg */
 enum {
     DN_FULL = 0,      /* whole subsampled Gauss-Newton matrix (Section 4.3) */
-    DN_BLOCKDIAG = 1  /* its diagonal blocks, one block per layer = W^m with b^m (Section 4.1) */
+    DN_BLOCKDIAG = 1, /* its diagonal blocks, one block per layer = W^m with b^m (Section 4.1) */
+    DN_PARTITION = 2  /* its diagonal blocks for the split structure given to dn_set_split (Section 3.1, 4.1) */
 };
 
 /* Human-readable text for an error code (static storage). */
@@ -136,14 +137,14 @@ int dn_cg(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter
           float* d, int* iters_host, double* resnorm_host);
 
 /*
- * dn_cg on the per-layer systems (DN_BLOCKDIAG) with the early termination of Section 4.4: besides each
+ * dn_cg on independent systems (mode DN_BLOCKDIAG or DN_PARTITION) with the early termination of Section 4.4: besides each
  * block's own test and max_iter, ALL blocks stop after the first iteration k >= cg_min at which the number
  * of blocks that have met their own test is >= r_percent/100 of the number of blocks (0 < r_percent <= 100;
  * cg_min >= 0).  On one GPU the blocks advance in lock-step, so "every partition has run cg_min iterations"
- * is k >= cg_min; the rule then only cuts iterations, it saves no waiting.  Outputs as dn_cg with
- * resnorm_host[0..L-1].  The host looks at the blocks' state after every iteration (one synchronisation each).
+ * is k >= cg_min; the rule then only cuts iterations, it saves no waiting.  Outputs as dn_cg with one
+ * resnorm_host entry per system.  The host looks at the blocks' state after every iteration (one synchronisation each).
  */
-int dn_cg_sync(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter, int cg_min,
+int dn_cg_sync(dn_ctx* ctx, const float* g, double lambda, double sigma, int max_iter, int mode, int cg_min,
                double r_percent, float* d, int* iters_host, double* resnorm_host);
 
 /*
@@ -174,10 +175,10 @@ typedef struct dn_newton_params {
     double eps;         /* determinant threshold of the two-variable system */
     double drop, boost; /* factors of the lambda rule, 0 < drop <= 1 <= boost */
     int cg_max;         /* >= 1 */
-    int mode;           /* DN_FULL or DN_BLOCKDIAG: matrix of the CG systems */
+    int mode;           /* DN_FULL, DN_BLOCKDIAG or DN_PARTITION: matrix of the CG systems */
     int combine;        /* nonzero: step 4 */
     int max_trials;     /* >= 1 */
-    int cg_min;         /* with mode DN_BLOCKDIAG and r_percent > 0: early termination as in dn_cg_sync */
+    int cg_min;         /* with independent systems and r_percent > 0: early termination as in dn_cg_sync */
     double r_percent;   /* <= 0: every block runs to its own test */
 } dn_newton_params;
 
@@ -193,6 +194,21 @@ typedef struct dn_newton_stats {
 
 int dn_newton_step(dn_ctx* ctx, float* theta, const float* X, const float* Y, int l, const int* S, int s,
                    float* d_prev, dn_newton_params* params, dn_newton_stats* stats_host);
+
+/*
+ * Split structure for DN_PARTITION (Section 3.1): groups[m], m = 0..L, is the number of contiguous,
+ * as-equal-as-possible neuron groups of layer m (1 <= groups[m] <= min(4, n_m)); group k of a layer with
+ * n neurons is [floor(k n / groups), floor((k+1) n / groups)).  The weights from group a of layer m-1 to
+ * group b of layer m form one partition; the biases of group b go with the partition of a = 0.  Partitions
+ * are numbered layer by layer, a outer, b inner; dn_num_partitions gives their count (sum of
+ * groups[m-1] * groups[m]).  Needs a bound workspace (an index map of n ints is uploaded); dn_bind
+ * forgets it.  With mode DN_PARTITION dn_gn_matvec applies the diagonal blocks of G^S over these
+ * partitions, dn_cg / dn_cg_sync solve the independent systems (resnorm_host then has
+ * dn_num_partitions entries), dn_newton_step uses them in its CG.  All groups[m] = 1 is DN_BLOCKDIAG.
+ * The products of this mode use general two-pass kernels (every hidden layer's block is streamed twice).
+ */
+int dn_set_split(dn_ctx* ctx, const int* groups);
+int dn_num_partitions(const dn_ctx* ctx);
 
 /*
  * Products with n_L > 16 and at least two hidden layers read each stored block ONCE per product by

@@ -14,6 +14,7 @@ import torch
 
 DN_FULL = 0
 DN_BLOCKDIAG = 1
+DN_PARTITION = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[ctypes.CDLL] = None
@@ -74,7 +75,9 @@ def load_library() -> ctypes.CDLL:
         "dn_jacobian_read": (i, [vp, i, vp]),
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
-        "dn_cg_sync": (i, [vp, vp, d, d, i, i, d, vp, P(i), P(d)]),
+        "dn_cg_sync": (i, [vp, vp, d, d, i, i, i, d, vp, P(i), P(d)]),
+        "dn_set_split": (i, [vp, P(i)]),
+        "dn_num_partitions": (i, [vp]),
         "dn_newton_step": (i, [vp, vp, vp, vp, i, vp, i, vp, P(NewtonParams), P(NewtonStats)]),
         "dn_set_stream_passes": (i, [vp, i]),
         "dn_set_spin_limit": (i, [vp, ctypes.c_uint]),
@@ -97,7 +100,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_cg_sync", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_cg_sync", "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
     "dn_profile_enable",
     "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
@@ -150,6 +153,19 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_split(self, groups: Sequence[int]) -> int:
+        """Split structure for DN_PARTITION (neuron groups per layer, Section 3.1); returns the partition count."""
+        arr = (ctypes.c_int * len(self.dims))(*[int(x) for x in groups])
+        if len(groups) != len(self.dims):
+            raise ValueError("one group count per layer, input layer included")
+        self._check(self._lib.dn_set_split(self._h, arr), "dn_set_split")
+        return int(self._lib.dn_num_partitions(self._h))
+
+    def num_systems(self, mode: int) -> int:
+        if mode == DN_PARTITION:
+            return int(self._lib.dn_num_partitions(self._h))
+        return self.L if mode == DN_BLOCKDIAG else 1
 
     # -- single-pass (team) kernel controls --------------------------------------------------
     def set_stream_passes(self, passes: int) -> None:
@@ -242,7 +258,7 @@ def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int
           d: torch.Tensor) -> Tuple[int, list]:
     """CG on (G^S + lam I) d = -g; returns (iterations, residual norms)."""
     iters = ctypes.c_int()
-    nres = ctx.L if mode == DN_BLOCKDIAG else 1
+    nres = ctx.num_systems(mode)
     res = (ctypes.c_double * max(nres, 1))()
     rc = ctx._lib.dn_cg(ctx._h, _dev_f32(g, "g", ctx.n), float(lam), float(sigma), int(max_iter), int(mode),
                         _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
@@ -251,14 +267,16 @@ def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int
 
 
 def dn_cg_sync(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int, cg_min: int,
-               r_percent: float, d: torch.Tensor) -> Tuple[int, list]:
-    """Per-layer CG with the joint early termination of Section 4.4; returns (iterations, residual norms)."""
+               r_percent: float, d: torch.Tensor, mode: int = DN_BLOCKDIAG) -> Tuple[int, list]:
+    """CG on independent systems with the joint early termination of Section 4.4; returns (iterations,
+    residual norms)."""
     iters = ctypes.c_int()
-    res = (ctypes.c_double * ctx.L)()
-    rc = ctx._lib.dn_cg_sync(ctx._h, _dev_f32(g, "g", ctx.n), float(lam), float(sigma), int(max_iter), int(cg_min),
-                             float(r_percent), _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
+    nres = max(ctx.num_systems(mode), 1)
+    res = (ctypes.c_double * nres)()
+    rc = ctx._lib.dn_cg_sync(ctx._h, _dev_f32(g, "g", ctx.n), float(lam), float(sigma), int(max_iter), int(mode),
+                             int(cg_min), float(r_percent), _dev_f32(d, "d", ctx.n), ctypes.byref(iters), res)
     ctx._check(rc, "dn_cg_sync")
-    return iters.value, [res[k] for k in range(ctx.L)]
+    return iters.value, [res[k] for k in range(nres)]
 
 
 def dn_newton_step(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor, S: torch.Tensor,

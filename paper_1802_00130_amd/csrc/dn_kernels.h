@@ -7,6 +7,8 @@
 #define DN_MAX_LAYERS 8
 #define DN_MAX_WSLOTS 16
 #define DN_MAX_PARTIALS 1024
+#define DN_MAX_SPLIT 4                                  // neuron groups per layer of a split structure
+#define DN_MAX_SEGS (DN_MAX_LAYERS * DN_MAX_SPLIT * DN_MAX_SPLIT)   // independent CG systems (partitions)
 
 namespace dn {
 
@@ -719,22 +721,21 @@ __global__ __launch_bounds__(256) void tn_reduce_kernel(const ReduceArgs a, cons
 struct CgSegs {
     int nseg;
     int chunk;                           // elements per work-group
-    long long off[DN_MAX_LAYERS + 1];    // segment k covers [off[k], off[k+1])
-    int cb[DN_MAX_LAYERS + 1];           // first work-group of segment k; cb[nseg] = grid size
+    long long off[DN_MAX_SEGS + 1];      // segment k covers [off[k], off[k+1])
+    int cb[DN_MAX_SEGS + 1];             // first work-group of segment k; cb[nseg] = grid size
 };
 
 struct CgState {                         // lives in device memory, one per iteration parity
-    double rho[DN_MAX_LAYERS];           // r^T r
-    double gnorm2[DN_MAX_LAYERS];        // g^T g
-    int active[DN_MAX_LAYERS];
-    int pad[DN_MAX_LAYERS];
+    double rho[DN_MAX_SEGS];             // r^T r
+    double gnorm2[DN_MAX_SEGS];          // g^T g
+    int active[DN_MAX_SEGS];
+    int pad[DN_MAX_SEGS];
 };
 
 __device__ __forceinline__ void cg_locate(const CgSegs& sg, int& seg, long long& lo, long long& hi) {
     seg = 0;
-#pragma unroll
-    for (int k = 1; k < DN_MAX_LAYERS; ++k)
-        if (k < sg.nseg && (int)blockIdx.x >= sg.cb[k]) seg = k;
+    for (int k = 1; k < sg.nseg; ++k)
+        if ((int)blockIdx.x >= sg.cb[k]) seg = k;
     lo = sg.off[seg] + (long long)((int)blockIdx.x - sg.cb[seg]) * sg.chunk;
     hi = lo + sg.chunk;
     if (hi > sg.off[seg + 1]) hi = sg.off[seg + 1];
@@ -831,6 +832,169 @@ __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const
     if (stop) return;
     const float beta = (float)(rho_new / st_cur->rho[seg]);
     for (long long e = lo + threadIdx.x; e < hi; e += 256) p[e] = r[e] + beta * p[e];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block-diagonal product for a general split structure (variable partitions of Section 3.1; Section 4.1).
+// Layer m has ga = split[m-1] input groups and gb = split[m] output groups; partition (a, b) owns the weights
+// from input group a to output group b (and, for a = 0, the biases of group b).  For each input group a the
+// inner sums over t in that group are Q^{m,a} (one dense product each); per partition
+//   r^{(a,b)}_i[u] = sum_{j in group b} P^m_i[u][j] q^{m,a,i}_j,     t^{m,a,i}_j = sum_u P^m_i[u][j] 2 r^{(a,b(j))}_i[u].
+// These two kernels are the general (two-pass) form; all hidden layers' blocks are streamed.
+struct PartArgs {
+    int L, s, nL;
+    int n[DN_MAX_LAYERS + 1];
+    long long ld[DN_MAX_LAYERS + 1];
+    int split[DN_MAX_LAYERS + 1];
+    int bound[DN_MAX_LAYERS + 1][DN_MAX_SPLIT + 1];   // bound[m][k]: first neuron of group k of layer m
+    int part_base[DN_MAX_LAYERS + 2];                 // first partition id of layer m (1..L)
+    const float* P[DN_MAX_LAYERS + 1];                // P[m], m = 1..L-1
+    const float* Qp[DN_MAX_LAYERS + 1];               // Q^{m,a}: Qp[m] + a * s * ld[m]
+    float* Tp[DN_MAX_LAYERS + 1];                     // T^{m,a}: Tp[m] + a * s * ld[m]
+    float* R;                                         // [partitions][s][ldr], hidden layers only
+    long long ldr;
+};
+
+__device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
+    int g = 0;
+#pragma unroll
+    for (int k = 1; k < DN_MAX_SPLIT; ++k)
+        if (k < groups && j >= bound[k]) g = k;
+    return g;
+}
+
+// work-group = (sample, block of 16 outputs); each wave takes whole rows u of every hidden layer's block
+__global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
+    constexpr int UB = 16;
+    const int ublocks = (a.nL + UB - 1) / UB;
+    const int i = blockIdx.x / ublocks;
+    const int u0 = (blockIdx.x - i * ublocks) * UB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long slab = (long long)a.s * a.ldr;
+    for (int uu = wave; uu < UB; uu += 4) {
+        const int u = u0 + uu;
+        if (u >= a.nL) break;
+        for (int m = 1; m < a.L; ++m) {
+            const int ga = a.split[m - 1], gb = a.split[m];
+            const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
+            double acc[DN_MAX_SPLIT][DN_MAX_SPLIT];
+#pragma unroll
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+#pragma unroll
+                for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] = 0.0;
+            for (int j = lane; j < a.n[m]; j += 64) {
+                const double pj = (double)prow[j];
+                const int bj = group_of(a.bound[m], gb, j);
+#pragma unroll
+                for (int x = 0; x < DN_MAX_SPLIT; ++x) {
+                    if (x < ga) {
+                        const double t = pj * (double)a.Qp[m][((long long)x * a.s + i) * a.ld[m] + j];
+#pragma unroll
+                        for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] += (y == bj) ? t : 0.0;
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+#pragma unroll
+                for (int y = 0; y < DN_MAX_SPLIT; ++y) {
+                    if (x < ga && y < gb) {
+                        const double t = wave_sum_d(acc[x][y]);
+                        if (lane == 0)
+                            a.R[(long long)(a.part_base[m] + x * gb + y) * slab + (long long)i * a.ldr + u] = (float)t;
+                    }
+                }
+        }
+    }
+}
+
+// work-group = (sample, layer, chunk of 256 columns); one thread per column.  Layer L: t^{L,a} = 2 q^{L,a}.
+__global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chunks_total) {
+    extern __shared__ float rbar[];          // [ga][gb][nL] of this layer
+    const int i = blockIdx.x / chunks_total;
+    int c = blockIdx.x - i * chunks_total;
+    int m = 1;
+    for (; m < a.L; ++m) {
+        const int cm = (a.n[m] + 255) >> 8;
+        if (c < cm) break;
+        c -= cm;
+    }
+    const int ga = a.split[m - 1];
+    if (m == a.L) {
+        // identity block: groups of outputs stay apart by themselves
+        for (int x = 0; x < ga; ++x)
+            for (int u = threadIdx.x; u < a.nL; u += 256) {
+                const long long e = ((long long)x * a.s + i) * a.ld[m] + u;
+                a.Tp[m][e] = 2.0f * a.Qp[m][e];
+            }
+        return;
+    }
+    const int gb = a.split[m];
+    const long long slab = (long long)a.s * a.ldr;
+    for (int e = threadIdx.x; e < ga * gb * a.nL; e += 256) {
+        const int pl = e / a.nL, u = e - pl * a.nL;
+        rbar[e] = 2.0f * a.R[(long long)(a.part_base[m] + pl) * slab + (long long)i * a.ldr + u];
+    }
+    __syncthreads();
+    const int j = (c << 8) + threadIdx.x;
+    if (j >= a.n[m]) return;
+    const int bj = group_of(a.bound[m], gb, j);
+    const float* __restrict__ pcol = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
+    double acc[DN_MAX_SPLIT];
+#pragma unroll
+    for (int x = 0; x < DN_MAX_SPLIT; ++x) acc[x] = 0.0;
+#pragma unroll 4
+    for (int u = 0; u < a.nL; ++u) {
+        const double pj = (double)pcol[(long long)u * a.ld[m]];
+#pragma unroll
+        for (int x = 0; x < DN_MAX_SPLIT; ++x)
+            if (x < ga) acc[x] += pj * (double)rbar[(x * gb + bj) * a.nL + u];
+    }
+#pragma unroll
+    for (int x = 0; x < DN_MAX_SPLIT; ++x)
+        if (x < ga) a.Tp[m][((long long)x * a.s + i) * a.ld[m] + j] = (float)acc[x];
+}
+
+// bias part of the sums over samples for a split structure: the biases of layer m belong to the partitions of
+// input group 0, so their sums are the column sums of T^{m,0}.  They go into column n_{m-1} of K-slice 0 of
+// the partial buffer; the same column of the other slices is cleared.  One thread per (layer, neuron).
+struct BiasSumArgs {
+    int L, s;
+    int n[DN_MAX_LAYERS + 1];
+    long long ld[DN_MAX_LAYERS + 1];
+    const float* T0[DN_MAX_LAYERS + 1];     // T^{m,0}
+    float* W[DN_MAX_LAYERS + 1];            // partial buffer of layer m: [splits][n_m][ldw]
+    long long ldw[DN_MAX_LAYERS + 1];
+    int splits;
+    int first[DN_MAX_LAYERS + 2];           // first global thread of layer m
+};
+
+__global__ __launch_bounds__(256) void bias_colsum_kernel(const BiasSumArgs a) {
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.first[a.L + 1]) return;
+    int m = 1;
+    for (int k = 2; k <= a.L; ++k)
+        if (g >= a.first[k]) m = k;
+    const int j = g - a.first[m];
+    double acc = 0.0;
+    for (int i = 0; i < a.s; ++i) acc += (double)a.T0[m][(long long)i * a.ld[m] + j];
+    const long long stride = (long long)a.n[m] * a.ldw[m];
+    float* w = a.W[m] + (long long)j * a.ldw[m] + a.n[m - 1];
+    w[0] = (float)acc;
+    for (int sidx = 1; sidx < a.splits; ++sidx) w[(long long)sidx * stride] = 0.f;
+}
+
+// dst[k] = src[perm[k]]  (gather)  /  dst[perm[k]] = src[k]  (scatter);  perm lists the theta indices
+// partition by partition, so that every partition is contiguous in the gathered order
+__global__ __launch_bounds__(256) void perm_gather_kernel(const float* __restrict__ src, const int* __restrict__ perm,
+                                                          float* __restrict__ dst, long long n, float scale) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256)
+        dst[e] = scale * src[perm[e]];
+}
+__global__ __launch_bounds__(256) void perm_scatter_kernel(const float* __restrict__ src, const int* __restrict__ perm,
+                                                           float* __restrict__ dst, long long n) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256)
+        dst[perm[e]] = src[e];
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -97,6 +97,16 @@ struct dn_ctx {
     size_t o_ng = 0, o_nd = 0, o_nGd = 0, o_nGdb = 0, o_ntheta = 0, o_npart = 0;
     // team kernel: partial vectors, folded vectors, counters, error word
     size_t o_texch = 0, o_terr = 0, o_ttp[DN_MAX_LAYERS + 1] = {0};
+    // split structure (DN_PARTITION): per input group Q^{m,a} / T^{m,a}, per partition r, the index map that
+    // lists theta partition by partition, CG vectors in that order and theta-layout operands of the product
+    size_t o_Qp[DN_MAX_LAYERS + 1] = {0}, o_Tp[DN_MAX_LAYERS + 1] = {0}, o_Rp = 0, o_perm = 0, o_gperm = 0,
+           o_dperm = 0, o_ptheta = 0, o_qtheta = 0;
+    int split[DN_MAX_LAYERS + 1] = {0};
+    int gbound[DN_MAX_LAYERS + 1][DN_MAX_SPLIT + 1] = {{0}};   // first neuron of each group
+    int part_base[DN_MAX_LAYERS + 2] = {0};
+    int nparts = 0;
+    long long part_off[DN_MAX_SEGS + 1] = {0};   // partition k covers [part_off[k], part_off[k+1]) of the index map
+    bool split_set = false;
     int team_rpt = 0;               // rows per thread of the team kernel for this n_L (0: team kernel not applicable)
     int team_nrs = 0;               // row slices
     long long tn_floats = 0;
@@ -370,6 +380,16 @@ void layout_workspace(dn_ctx* c) {
                 c->o_ttp[m] = take(cur, sizeof(float) * (size_t)c->team_nrs * c->s_max * c->ld[m]);
     }
     c->o_terr = take(cur, 256);
+    for (int m = 1; m <= L; ++m) {
+        c->o_Qp[m] = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * c->s_max * c->ld[m]);
+        c->o_Tp[m] = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * c->s_max * c->ld[m]);
+    }
+    c->o_Rp = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * DN_MAX_SPLIT * std::max(1, L - 1) * c->s_max * c->ldr);
+    c->o_perm = take(cur, sizeof(int) * (size_t)round_up(c->n, 64));
+    c->o_gperm = take(cur, nvec);
+    c->o_dperm = take(cur, nvec);
+    c->o_ptheta = take(cur, nvec);
+    c->o_qtheta = take(cur, nvec);
     c->ws_bytes = cur;
 }
 
@@ -590,8 +610,11 @@ int team_status(dn_ctx* c) {
     return err ? DN_ETIMEOUT : DN_OK;
 }
 
+int gn_matvec_part(dn_ctx* c, const float* v, float* out);
+
 // out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
 int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
+    if (mode == DN_PARTITION) return c->split_set ? gn_matvec_part(c, v, out) : DN_ESTATE;
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
     StreamArgs a;
     fill_stream_args(c, a, mode);
@@ -743,7 +766,10 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
 
 void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
     std::memset(&sg, 0, sizeof(sg));
-    if (mode == DN_BLOCKDIAG) {
+    if (mode == DN_PARTITION) {
+        sg.nseg = c->nparts;
+        for (int k = 0; k <= c->nparts; ++k) sg.off[k] = c->part_off[k];
+    } else if (mode == DN_BLOCKDIAG) {
         sg.nseg = c->L;
         for (int m = 1; m <= c->L; ++m) sg.off[m - 1] = c->woff[m];
         sg.off[c->L] = c->n;
@@ -769,7 +795,128 @@ void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
     sg.cb[sg.nseg] = b;
 }
 
-bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG; }
+bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG && mode != DN_PARTITION; }
+
+// Product over the partitions of the split structure (Section 3.1, 4.1), general two-pass form
+int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
+    const int L = c->L, s = c->s_cur, nL = c->dims[L];
+    PartArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.L = L; a.s = s; a.nL = nL;
+    for (int m = 0; m <= L; ++m) {
+        a.n[m] = c->dims[m];
+        a.ld[m] = c->ld[m];
+        a.split[m] = c->split[m];
+        for (int k = 0; k <= DN_MAX_SPLIT; ++k) a.bound[m][k] = c->gbound[m][k];
+    }
+    for (int m = 1; m <= L + 1; ++m) a.part_base[m] = c->part_base[m];
+    for (int m = 1; m < L; ++m) a.P[m] = c->fptr(c->o_P[m]);
+    for (int m = 1; m <= L; ++m) {
+        a.Qp[m] = c->fptr(c->o_Qp[m]);
+        a.Tp[m] = c->fptr(c->o_Tp[m]);
+    }
+    a.R = c->fptr(c->o_Rp);
+    a.ldr = c->ldr;
+    // 1. inner sums over t, one product per (layer, input group); the bias term rides with group 0
+    {
+        GemmGroup g;
+        g.nprob = 0;
+        auto flush = [&]() -> int {
+            if (g.nprob == 0) return DN_OK;
+            ProfScope ps(c, KC_GEMM_Q);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 64, 1, c->stream)));
+            DN_HIP(c, ps.end());
+            g.nprob = 0;
+            return DN_OK;
+        };
+        for (int m = 1; m <= L; ++m)
+            for (int x = 0; x < c->split[m - 1]; ++x) {
+                const int t0 = c->gbound[m - 1][x], t1 = c->gbound[m - 1][x + 1];
+                GemmProblem& p = g.p[g.nprob++];
+                p = mk_problem(c->fptr(c->o_ZS[m - 1]) + t0, c->ld[m - 1], v + c->woff[m] + t0, c->dims[m - 1],
+                               c->fptr(c->o_Qp[m]) + (long long)x * s * c->ld[m], c->ld[m], s, c->dims[m], t1 - t0);
+                if (x == 0) p.bias = v + c->boff[m];
+                if (g.nprob == DN_MAX_GROUP) {
+                    const int rc = flush();
+                    if (rc != DN_OK) return rc;
+                }
+            }
+        const int rc = flush();
+        if (rc != DN_OK) return rc;
+    }
+    // 2. the two passes over the stored blocks
+    if (L >= 2) {
+        ProfScope ps(c, KC_JV);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 16)), dim3(256), 0, c->stream, a);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    {
+        ProfScope ps(c, KC_JTV);
+        DN_HIP(c, ps.err);
+        int chunks = 1;
+        for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 256);
+        int most = 1;
+        for (int m = 1; m < L; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
+        const size_t lds = sizeof(float) * (size_t)most * nL;
+        hipLaunchKernelGGL(jtv_part_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256), lds, c->stream, a,
+                           chunks);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // 3. sums over samples, one product per (layer, input group) into that group's columns; bias sums apart
+    TnPlan pl = plan_tn(c, s, true, 0);
+    if (pl.total > c->tn_floats) return DN_ENOSPC;
+    {
+        GemmGroup g;
+        g.nprob = 0;
+        auto flush = [&]() -> int {
+            if (g.nprob == 0) return DN_OK;
+            ProfScope ps(c, KC_GEMM_TN_MATVEC);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+            DN_HIP(c, ps.end());
+            g.nprob = 0;
+            return DN_OK;
+        };
+        for (int m = 1; m <= L; ++m)
+            for (int x = 0; x < c->split[m - 1]; ++x) {
+                const int t0 = c->gbound[m - 1][x], t1 = c->gbound[m - 1][x + 1];
+                GemmProblem& p = g.p[g.nprob++];
+                p = mk_problem(c->fptr(c->o_Tp[m]) + (long long)x * s * c->ld[m], c->ld[m], c->fptr(c->o_ZS[m - 1]) + t0,
+                               c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m] + t0, c->ldw[m], c->dims[m], t1 - t0, s);
+                p.split_stride = (long long)c->dims[m] * c->ldw[m];
+                if (g.nprob == DN_MAX_GROUP) {
+                    const int rc = flush();
+                    if (rc != DN_OK) return rc;
+                }
+            }
+        const int rc = flush();
+        if (rc != DN_OK) return rc;
+        BiasSumArgs ba;
+        std::memset(&ba, 0, sizeof(ba));
+        ba.L = L; ba.s = s; ba.splits = pl.splits;
+        int threads = 0;
+        for (int m = 0; m <= L; ++m) { ba.n[m] = c->dims[m]; ba.ld[m] = c->ld[m]; }
+        for (int m = 1; m <= L; ++m) {
+            ba.T0[m] = c->fptr(c->o_Tp[m]);
+            ba.W[m] = c->fptr(c->o_tn) + pl.offset[m];
+            ba.ldw[m] = c->ldw[m];
+            ba.first[m] = threads;
+            threads += c->dims[m];
+        }
+        ba.first[L + 1] = threads;
+        ProfScope ps(c, KC_TN_REDUCE);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(bias_colsum_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, c->stream, ba);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // 4. fold slices, scale by 1/|S|, add v/C
+    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s);
+}
 
 }  // namespace
 
@@ -846,6 +993,7 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     c->prepped = false;
     c->team_clean = false;
     c->team_used = false;
+    c->split_set = false;
     // size of the chip, for kernels whose grid must be resident all at once (default kept if no device answers)
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -1027,9 +1175,24 @@ namespace {
 // CG of dn_cg / dn_cg_sync; r_percent <= 0 switches the joint termination of Section 4.4 off
 int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, int cg_min, double r_percent,
            float* d, int* iters_host, double* resnorm_host) {
+    if (mode == DN_PARTITION && !c->split_set) return DN_ESTATE;
     CgSegs sg;
     build_segs(c, mode, sg);
     const int grid = sg.cb[sg.nseg];
+    // With a split structure the CG vectors live in partition-major order (every partition contiguous, see
+    // dn_set_split); the product takes and returns theta-layout vectors, so p is scattered before and q
+    // gathered after every product.
+    const bool part = mode == DN_PARTITION;
+    const int* perm = reinterpret_cast<const int*>(c->ws + c->o_perm);
+    const int vgrid = grid_for(c->n);
+    float* d_cg = part ? c->fptr(c->o_dperm) : d;
+    const float* g_cg = g;
+    if (part) {
+        hipLaunchKernelGGL(perm_gather_kernel, dim3(vgrid), dim3(256), 0, c->stream, g, perm, c->fptr(c->o_gperm), c->n,
+                           1.0f);
+        DN_HIP(c, hipGetLastError());
+        g_cg = c->fptr(c->o_gperm);
+    }
     float* r = c->fptr(c->o_r);
     float* p = c->fptr(c->o_p);
     float* q = c->fptr(c->o_q);
@@ -1041,7 +1204,7 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
     {
         ProfScope ps(c, KC_CG_VEC);
         DN_HIP(c, ps.err);
-        hipLaunchKernelGGL(cg_init_kernel, dim3(grid), dim3(256), 0, c->stream, sg, g, d, r, p, part0);
+        hipLaunchKernelGGL(cg_init_kernel, dim3(grid), dim3(256), 0, c->stream, sg, g_cg, d_cg, r, p, part0);
         DN_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(cg_init_state_kernel, dim3(1), dim3(256), 0, c->stream, sg, part0, st);
         DN_HIP(c, hipGetLastError());
@@ -1063,8 +1226,20 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
     int iters = 0;
     bool active = any_active(hst);
     while (iters < max_iter && active) {
-        int rc = gn_matvec(c, p, q, mode);
-        if (rc != DN_OK) return rc;
+        int rc;
+        if (part) {
+            hipLaunchKernelGGL(perm_scatter_kernel, dim3(vgrid), dim3(256), 0, c->stream, p, perm, c->fptr(c->o_ptheta),
+                               c->n);
+            DN_HIP(c, hipGetLastError());
+            rc = gn_matvec(c, c->fptr(c->o_ptheta), c->fptr(c->o_qtheta), mode);
+            if (rc != DN_OK) return rc;
+            hipLaunchKernelGGL(perm_gather_kernel, dim3(vgrid), dim3(256), 0, c->stream, c->fptr(c->o_qtheta), perm, q,
+                               c->n, 1.0f);
+            DN_HIP(c, hipGetLastError());
+        } else {
+            rc = gn_matvec(c, p, q, mode);
+            if (rc != DN_OK) return rc;
+        }
         const CgState* cur = st + (iters & 1);
         CgState* nxt = st + ((iters + 1) & 1);
         {
@@ -1073,7 +1248,7 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
             hipLaunchKernelGGL(cg_dot_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda, part1);
             DN_HIP(c, hipGetLastError());
             hipLaunchKernelGGL(cg_update_dr_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, part1, p, q,
-                               (float)lambda, d, r, part2);
+                               (float)lambda, d_cg, r, part2);
             DN_HIP(c, hipGetLastError());
             hipLaunchKernelGGL(cg_update_p_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, nxt, part2,
                                sigma * sigma, r, p);
@@ -1087,6 +1262,10 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
             active = any_active(hst);
             if (joint && joint_stop(hst, iters)) break;
         }
+    }
+    if (part) {
+        hipLaunchKernelGGL(perm_scatter_kernel, dim3(vgrid), dim3(256), 0, c->stream, d_cg, perm, d, c->n);
+        DN_HIP(c, hipGetLastError());
     }
     DN_HIP(c, hipMemcpyAsync(&hst, st + (iters & 1), sizeof(CgState), hipMemcpyDeviceToHost, c->stream));
     DN_HIP(c, hipStreamSynchronize(c->stream));
@@ -1105,13 +1284,65 @@ int dn_cg(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, 
     return cg_run(c, g, lambda, sigma, max_iter, mode, 0, 0.0, d, iters_host, resnorm_host);
 }
 
-int dn_cg_sync(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int cg_min, double r_percent,
-               float* d, int* iters_host, double* resnorm_host) {
+int dn_cg_sync(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter, int mode, int cg_min,
+               double r_percent, float* d, int* iters_host, double* resnorm_host) {
     if (!c || !g || !d || !iters_host || !resnorm_host || max_iter < 1 || cg_min < 0 || !(lambda >= 0.0) ||
-        !(sigma >= 0.0) || !(r_percent > 0.0 && r_percent <= 100.0))
+        !(sigma >= 0.0) || !(r_percent > 0.0 && r_percent <= 100.0) || (mode != DN_BLOCKDIAG && mode != DN_PARTITION))
         return DN_EINVAL;
     if (!c->bound || !c->prepped) return DN_ESTATE;
-    return cg_run(c, g, lambda, sigma, max_iter, DN_BLOCKDIAG, cg_min, r_percent, d, iters_host, resnorm_host);
+    return cg_run(c, g, lambda, sigma, max_iter, mode, cg_min, r_percent, d, iters_host, resnorm_host);
+}
+
+int dn_num_partitions(const dn_ctx* c) { return (c && c->split_set) ? c->nparts : 0; }
+
+int dn_set_split(dn_ctx* c, const int* groups) {
+    if (!c || !groups) return DN_EINVAL;
+    const int L = c->L;
+    for (int m = 0; m <= L; ++m)
+        if (groups[m] < 1 || groups[m] > DN_MAX_SPLIT || groups[m] > c->dims[m]) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    c->split_set = false;
+    int np = 0;
+    for (int m = 0; m <= L; ++m) {
+        c->split[m] = groups[m];
+        for (int k = 0; k <= DN_MAX_SPLIT; ++k)
+            c->gbound[m][k] = (int)((long long)std::min(k, groups[m]) * c->dims[m] / groups[m]);
+        if (m >= 1) {
+            c->part_base[m] = np;
+            np += groups[m - 1] * groups[m];
+        }
+    }
+    c->part_base[L + 1] = np;
+    c->nparts = np;
+    // index map: theta indices partition by partition (layer, input group a, output group b; inside a
+    // partition the weights row by row, then the biases for a = 0)
+    std::vector<int> perm;
+    try {
+        perm.resize((size_t)c->n);
+    } catch (const std::bad_alloc&) {
+        return DN_ENOMEM;
+    }
+    long long k = 0;
+    int pid = 0;
+    for (int m = 1; m <= L; ++m) {
+        const int nprev = c->dims[m - 1];
+        for (int a = 0; a < groups[m - 1]; ++a)
+            for (int b = 0; b < groups[m]; ++b) {
+                c->part_off[pid++] = k;
+                for (int j = c->gbound[m][b]; j < c->gbound[m][b + 1]; ++j)
+                    for (int t = c->gbound[m - 1][a]; t < c->gbound[m - 1][a + 1]; ++t)
+                        perm[(size_t)k++] = (int)(c->woff[m] + (long long)j * nprev + t);
+                if (a == 0)
+                    for (int j = c->gbound[m][b]; j < c->gbound[m][b + 1]; ++j) perm[(size_t)k++] = (int)(c->boff[m] + j);
+            }
+    }
+    c->part_off[pid] = k;
+    if (k != c->n) return DN_EINVAL;
+    DN_HIP(c, hipMemcpyAsync(c->ws + c->o_perm, perm.data(), sizeof(int) * (size_t)c->n, hipMemcpyHostToDevice,
+                             c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    c->split_set = true;
+    return DN_OK;
 }
 
 int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int l, const int* S, int s, float* d_prev,
@@ -1141,8 +1372,8 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
     if (rc != DN_OK) return rc;
     rc = dn_jacobian_prep(c, theta, X, l, S, s);
     if (rc != DN_OK) return rc;
-    double resn[DN_MAX_LAYERS];
-    const bool joint = prm->mode == DN_BLOCKDIAG && prm->r_percent > 0.0;
+    double resn[DN_MAX_SEGS];
+    const bool joint = prm->mode != DN_FULL && prm->r_percent > 0.0;
     rc = cg_run(c, g, prm->lambda, prm->sigma, prm->cg_max, prm->mode, joint ? prm->cg_min : 0,
                 joint ? prm->r_percent : 0.0, d, &st->cg_iters, resn);
     if (rc != DN_OK) return rc;

@@ -75,9 +75,15 @@ def test_call_order_and_argument_errors(lib):
     assert lib.dn_gn_matvec(h, fake, fake, 5) == -1
     assert lib.dn_cg(h, fake, 1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
     assert lib.dn_cg(h, fake, -1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
-    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 0, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
-    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 0, 0.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
-    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, -1, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 1, 0, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 1, 0, 0.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 1, -1, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
+    assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 0, 0, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -1   # full mode
+    assert lib.dn_gn_matvec(h, fake, fake, 2) == -3                                  # no Jacobian / no split structure
+    assert lib.dn_num_partitions(h) == 0
+    assert lib.dn_set_split(h, (ctypes.c_int * 3)(1, 6, 1)) == -1                    # more groups than allowed / neurons
+    assert lib.dn_set_split(h, (ctypes.c_int * 3)(0, 1, 1)) == -1
+    assert lib.dn_set_split(h, None) == -1
     assert lib.dn_jacobian_read(h, 2, fake) == -1
     assert lib.dn_jacobian_read(h, 1, fake) == -3
     prm = binding.NewtonParams(1.0, 1e-3, 1e-4, 1e-5, 2.0 / 3.0, 1.5, 10, 0, 1, 30, 0, 0.0)
