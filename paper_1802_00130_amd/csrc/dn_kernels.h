@@ -863,9 +863,9 @@ __device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
     return g;
 }
 
-// work-group = (sample, block of 16 outputs); each wave takes whole rows u of every hidden layer's block
+// work-group = (sample, block of 4 outputs); each wave takes one row u of every hidden layer's block
 __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
-    constexpr int UB = 16;
+    constexpr int UB = 4;
     const int ublocks = (a.nL + UB - 1) / UB;
     const int i = blockIdx.x / ublocks;
     const int u0 = (blockIdx.x - i * ublocks) * UB;
@@ -882,15 +882,28 @@ __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
             for (int x = 0; x < DN_MAX_SPLIT; ++x)
 #pragma unroll
                 for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] = 0.0;
-            for (int j = lane; j < a.n[m]; j += 64) {
-                const double pj = (double)prow[j];
-                const int bj = group_of(a.bound[m], gb, j);
+            // four columns at a time (rows are 16-byte aligned and padded to a multiple of 4 floats; the padding of
+            // P and Q holds no data, so the last, partial group of four is masked); a group boundary may fall
+            // inside a group of four, hence the per-column group index
+            const int nm4 = (a.n[m] + 3) >> 2;
+            for (int c4 = lane; c4 < nm4; c4 += 64) {
+                const int j = 4 * c4;
+                const float4 p4 = *reinterpret_cast<const float4*>(prow + j);
+                const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
+                int bj[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bj[e] = (j + e < a.n[m]) ? group_of(a.bound[m], gb, j + e) : -1;
 #pragma unroll
                 for (int x = 0; x < DN_MAX_SPLIT; ++x) {
                     if (x < ga) {
-                        const double t = pj * (double)a.Qp[m][((long long)x * a.s + i) * a.ld[m] + j];
+                        const float4 q4 = *reinterpret_cast<const float4*>(a.Qp[m] + ((long long)x * a.s + i) * a.ld[m] + j);
+                        const float qe[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
-                        for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] += (y == bj) ? t : 0.0;
+                        for (int e = 0; e < 4; ++e) {
+                            const double t = bj[e] >= 0 ? (double)pe[e] * (double)qe[e] : 0.0;
+#pragma unroll
+                            for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] += (y == bj[e]) ? t : 0.0;
+                        }
                     }
                 }
             }
@@ -956,8 +969,9 @@ __global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chu
 }
 
 // bias part of the sums over samples for a split structure: the biases of layer m belong to the partitions of
-// input group 0, so their sums are the column sums of T^{m,0}.  They go into column n_{m-1} of K-slice 0 of
-// the partial buffer; the same column of the other slices is cleared.  One thread per (layer, neuron).
+// input group 0, so their sums are the column sums of T^{m,0}.  K-slice k of the samples puts its sum into
+// column n_{m-1} of slice k of the partial buffer, where the products with a column of ones put theirs in
+// the other modes.  Work-group = (layer, 16 neurons, K-slice); 16 threads per neuron share the samples.
 struct BiasSumArgs {
     int L, s;
     int n[DN_MAX_LAYERS + 1];
@@ -965,23 +979,30 @@ struct BiasSumArgs {
     const float* T0[DN_MAX_LAYERS + 1];     // T^{m,0}
     float* W[DN_MAX_LAYERS + 1];            // partial buffer of layer m: [splits][n_m][ldw]
     long long ldw[DN_MAX_LAYERS + 1];
-    int splits;
-    int first[DN_MAX_LAYERS + 2];           // first global thread of layer m
+    int splits, k_per_split;
+    int first[DN_MAX_LAYERS + 2];           // first 16-neuron chunk of layer m
 };
 
 __global__ __launch_bounds__(256) void bias_colsum_kernel(const BiasSumArgs a) {
-    const int g = blockIdx.x * 256 + threadIdx.x;
-    if (g >= a.first[a.L + 1]) return;
+    __shared__ double red[16][17];
+    const int chunk = blockIdx.x / a.splits, sidx = blockIdx.x - chunk * a.splits;
     int m = 1;
     for (int k = 2; k <= a.L; ++k)
-        if (g >= a.first[k]) m = k;
-    const int j = g - a.first[m];
+        if (chunk >= a.first[k]) m = k;
+    const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
+    const int j = (chunk - a.first[m]) * 16 + c;
+    const int i_lo = sidx * a.k_per_split, i_hi = min(a.s, i_lo + a.k_per_split);
     double acc = 0.0;
-    for (int i = 0; i < a.s; ++i) acc += (double)a.T0[m][(long long)i * a.ld[m] + j];
-    const long long stride = (long long)a.n[m] * a.ldw[m];
-    float* w = a.W[m] + (long long)j * a.ldw[m] + a.n[m - 1];
-    w[0] = (float)acc;
-    for (int sidx = 1; sidx < a.splits; ++sidx) w[(long long)sidx * stride] = 0.f;
+    if (j < a.n[m])
+        for (int i = i_lo + r; i < i_hi; i += 16) acc += (double)a.T0[m][(long long)i * a.ld[m] + j];
+    red[r][c] = acc;
+    __syncthreads();
+    if (r == 0 && j < a.n[m]) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += red[k][c];
+        a.W[m][(long long)sidx * a.n[m] * a.ldw[m] + (long long)j * a.ldw[m] + a.n[m - 1]] = (float)t;
+    }
 }
 
 // dst[k] = src[perm[k]]  (gather)  /  dst[perm[k]] = src[k]  (scatter);  perm lists the theta indices

@@ -849,7 +849,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
     if (L >= 2) {
         ProfScope ps(c, KC_JV);
         DN_HIP(c, ps.err);
-        hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 16)), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 4)), dim3(256), 0, c->stream, a);
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     }
@@ -898,19 +898,21 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         BiasSumArgs ba;
         std::memset(&ba, 0, sizeof(ba));
         ba.L = L; ba.s = s; ba.splits = pl.splits;
-        int threads = 0;
+        // the K-slices are those of the products above (finalize_group: slice length rounded up to the K tile)
+        ba.k_per_split = (int)round_up(cdiv(s, pl.splits), 16);
+        int chunks = 0;
         for (int m = 0; m <= L; ++m) { ba.n[m] = c->dims[m]; ba.ld[m] = c->ld[m]; }
         for (int m = 1; m <= L; ++m) {
             ba.T0[m] = c->fptr(c->o_Tp[m]);
             ba.W[m] = c->fptr(c->o_tn) + pl.offset[m];
             ba.ldw[m] = c->ldw[m];
-            ba.first[m] = threads;
-            threads += c->dims[m];
+            ba.first[m] = chunks;
+            chunks += cdiv(c->dims[m], 16);
         }
-        ba.first[L + 1] = threads;
+        ba.first[L + 1] = chunks;
         ProfScope ps(c, KC_TN_REDUCE);
         DN_HIP(c, ps.err);
-        hipLaunchKernelGGL(bias_colsum_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, c->stream, ba);
+        hipLaunchKernelGGL(bias_colsum_kernel, dim3(chunks * pl.splits), dim3(256), 0, c->stream, ba);
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     }
