@@ -123,6 +123,15 @@ int dn_jacobian_read(dn_ctx* ctx, int m, float* P_out);
 int dn_gn_matvec(dn_ctx* ctx, const float* v, float* out, int mode);
 
 /*
+ * out = G^S v (whole matrix, no damping) WITHOUT the stored blocks: J^i v by differentiating the forward pass
+ * along v (the R-operator approach that Section 2.2 mentions and Section 3 sets aside as sequential over the
+ * layers), then (J^i)^T by back-propagation, all as dense products on the subsample's activations kept by
+ * dn_jacobian_prep.  Same result as dn_gn_matvec(DN_FULL) up to rounding; on one GPU it is an independent
+ * cross-check and the comparator for what storing the blocks costs or saves.  Needs a prior dn_jacobian_prep.
+ */
+int dn_gn_matvec_rop(dn_ctx* ctx, const float* v, float* out);
+
+/*
  * Conjugate gradient on (G^S + lambda I) d = -g  (Section 2.2, Section 4.3), d_0 = 0, no
  * preconditioner, at most max_iter >= 1 iterations.  After every iteration the recurrence residual
  * r is tested: stop when ||r|| <= sigma ||g||  (Section 4.1).  sigma = 0 runs exactly max_iter

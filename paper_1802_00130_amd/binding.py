@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
         "dn_jacobian_prep": (i, [vp, vp, vp, i, vp, i]),
         "dn_jacobian_read": (i, [vp, i, vp]),
         "dn_gn_matvec": (i, [vp, vp, vp, i]),
+        "dn_gn_matvec_rop": (i, [vp, vp, vp]),
         "dn_cg": (i, [vp, vp, d, d, i, i, vp, P(i), P(d)]),
         "dn_cg_sync": (i, [vp, vp, d, d, i, i, i, d, vp, P(i), P(d)]),
         "dn_set_split": (i, [vp, P(i)]),
@@ -100,7 +101,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_cg", "dn_cg_sync", "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync", "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
     "dn_profile_enable",
     "dn_profile_select",
     "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
@@ -252,6 +253,12 @@ def dn_gn_matvec(ctx: Context, v: torch.Tensor, out: torch.Tensor, mode: int = D
     """out = G^S v, full or per-layer block-diagonal (Sections 4.1-4.3)."""
     rc = ctx._lib.dn_gn_matvec(ctx._h, _dev_f32(v, "v", ctx.n), _dev_f32(out, "out", ctx.n), int(mode))
     ctx._check(rc, "dn_gn_matvec")
+
+
+def dn_gn_matvec_rop(ctx: Context, v: torch.Tensor, out: torch.Tensor) -> None:
+    """out = G^S v without the stored blocks (forward-mode pass, then back-propagation; Section 2.2's alternative)."""
+    rc = ctx._lib.dn_gn_matvec_rop(ctx._h, _dev_f32(v, "v", ctx.n), _dev_f32(out, "out", ctx.n))
+    ctx._check(rc, "dn_gn_matvec_rop")
 
 
 def dn_cg(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter: int, mode: int,

@@ -43,8 +43,9 @@ enum OperandLayout { KC = 0, RC = 1, RT = 2 };
 __device__ const float dn_ones4[4] = {1.f, 1.f, 1.f, 1.f};
 
 // Epilogue of a problem, applied in this order to every output element (m, n):
-//   x = alpha * acc;  x += bias[n] (if bias);  x = 1/(1+exp(-x)) (if sigmoid);
-//   x *= z(1-z) with z = aux[(m / auxdiv) * ldaux + n] (if aux);  x += add[m * ldadd + n] (if add).
+//   x = alpha * acc;  x += bias[n] (if bias);  x += pre[m * ldpre + n] (if pre);  x = 1/(1+exp(-x)) (if sigmoid);
+//   x *= z(1-z) with z = aux[(m / auxdiv) * ldaux + n] (if aux);  x += add[m * ldadd + n] (if add);
+//   x += C[m][n] of the same K-slice (if accumulate).
 
 struct GemmProblem {
     const float* A;
@@ -53,7 +54,8 @@ struct GemmProblem {
     const float* bias;   // nullable: length N
     const float* aux;    // nullable: activations z whose sigma' = z(1-z) scales the result
     const float* add;    // nullable: matrix added last (may be C itself)
-    long long lda, ldb, ldc, ldaux, ldadd;
+    const float* pre;    // nullable: matrix added before the activation / sigma' scaling (may be C itself)
+    long long lda, ldb, ldc, ldaux, ldadd, ldpre;
     float alpha;         // scale of the accumulated product
     int sigmoid;         // 1: logistic function after the bias
     long long split_stride;  // elements between the C outputs of consecutive K-slices
@@ -638,7 +640,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 
     // ---- epilogue: lane holds column n = .. + r and rows 8*(e/4) + 4*h + e%4 of each 32x32 block ----
     float* __restrict__ Cb = P.C + (long long)split * P.split_stride;
-    const bool plain = !P.sigmoid && !P.aux && !P.add && !P.accumulate;      // uniform: keep the common case branch-free
+    const bool plain = !P.sigmoid && !P.aux && !P.add && !P.accumulate && !P.pre;   // uniform: keep the common case branch-free
     const float alpha = P.alpha;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -659,6 +661,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
                     const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
                     if (m >= P.M) continue;
                     float x = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
+                    if (P.pre) x += P.pre[(long long)m * P.ldpre + n];
                     if (P.sigmoid) x = sigmoidf_fast(x);
                     if (P.aux) {
                         const float z = P.aux[(long long)(m / P.auxdiv) * P.ldaux + n];

@@ -43,6 +43,7 @@ enum KernelClass {
     KC_JTV,               // product: P^T r
     KC_JV_JTV_TEAM,       // product: both passes over P, one read, teams of work-groups
     KC_GEMM_IMPLICIT,     // product: the two small dense products that stand in for block L-1
+    KC_GEMM_ROP,          // product without stored blocks: forward-mode and back-propagation sweeps
     KC_TN_REDUCE,         // slice fold + regularisation term
     KC_JAC_INIT,
     KC_GATHER,
@@ -53,7 +54,7 @@ enum KernelClass {
 
 const char* const kClassNames[KC_COUNT] = {
     "gemm_forward", "gemm_backprop", "gemm_tn_grad", "gemm_jacobian_prep", "gemm_q_matvec", "gemm_tn_matvec",
-    "jv_jtv_fused", "jv_rows", "jtv_cols", "jv_jtv_team", "gemm_implicit_block", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
+    "jv_jtv_fused", "jv_rows", "jtv_cols", "jv_jtv_team", "gemm_implicit_block", "gemm_rop_sweeps", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
 
 inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -91,6 +92,7 @@ struct dn_ctx {
     size_t o_Qb = 0;           // second half of one layer's Q when its sum over t is cut in two
     size_t o_T[DN_MAX_LAYERS + 1] = {0};
     size_t o_AL = 0;
+    size_t o_thS = 0;          // copy of theta taken by dn_jacobian_prep (the product without stored blocks needs A^m)
     size_t o_WT = 0;           // W^m = (A^m)^T for m = 2..L, dense, at the theta offsets of A^m
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
     // outer Newton iteration: gradient, direction, G d, G d_prev, trial point; partial sums of 5 dot products
@@ -349,6 +351,7 @@ void layout_workspace(dn_ctx* c) {
     }
     c->o_AL = take(cur, sizeof(float) * (size_t)c->dims[L] * c->ld[L >= 2 ? L - 1 : 0]);
     c->o_WT = take(cur, sizeof(float) * (size_t)round_up(c->n, 64));
+    c->o_thS = take(cur, sizeof(float) * (size_t)round_up(c->n, 64));
     c->o_R = take(cur, sizeof(float) * (size_t)L * c->s_max * c->ldr);
     long long tn = plan_tn(c, c->s_max, true, 0).total;
     for (int m = 1; m <= L; ++m) tn = std::max(tn, plan_tn(c, c->l_max, false, m).total);
@@ -1132,10 +1135,11 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     }
-    if (L >= 3) {
-        rc = transpose_weights(c, theta, 2, L - 1);
+    if (L >= 2) {
+        rc = transpose_weights(c, theta, 2, L);
         if (rc != DN_OK) return rc;
     }
+    DN_HIP(c, hipMemcpyAsync(c->fptr(c->o_thS), theta, sizeof(float) * (size_t)c->n, hipMemcpyDeviceToDevice, c->stream));
     // P^{m-1} = (P^m (W^m)^T) * sigma'(s^{m-1}):  the n_L backward sweeps of all samples as one product
     for (int m = L - 1; m >= 2; --m) {
         GemmGroup g;
@@ -1482,6 +1486,89 @@ int dn_sync_status(dn_ctx* c) {
     if (!c->bound) return DN_ESTATE;
     DN_HIP(c, hipStreamSynchronize(c->stream));
     return team_status(c);
+}
+
+int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
+    if (!c || !v || !out) return DN_EINVAL;
+    if (!c->bound || !c->prepped) return DN_ESTATE;
+    const int L = c->L, s = c->s_cur;
+    const float* th = c->fptr(c->o_thS);
+    // 1. inner sums over t for every layer, Q^m = Z^{m-1} V^m + vb^m; layer 1's result is at once the
+    //    derivative of z^1 along v:  zdot^1 = sigma'(s^1) * Q^1
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            g.p[m - 1] = mk_problem(c->fptr(c->o_ZS[m - 1]), c->ld[m - 1], v + c->woff[m], c->dims[m - 1],
+                                    c->fptr(c->o_Q[m]), c->ld[m], s, c->dims[m], c->dims[m - 1]);
+            g.p[m - 1].bias = v + c->boff[m];
+        }
+        if (L >= 2) {
+            g.p[0].aux = c->fptr(c->o_ZS[1]);
+            g.p[0].ldaux = c->ld[1];
+        }
+        const int tile = pick_tile(g, true);
+        ProfScope ps(c, KC_GEMM_Q);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 2. forward sweep of the derivative: zdot^m = sigma'(s^m) * (Q^m + zdot^{m-1} W^m), in place in Q^m;
+    //    at the output layer sigma' = 1 and Q^L becomes J^i v
+    for (int m = 2; m <= L; ++m) {
+        GemmGroup g;
+        g.nprob = 1;
+        GemmProblem& p = g.p[0];
+        p = mk_problem(c->fptr(c->o_Q[m - 1]), c->ld[m - 1], th + c->woff[m], c->dims[m - 1], c->fptr(c->o_Q[m]),
+                       c->ld[m], s, c->dims[m], c->dims[m - 1]);
+        p.pre = c->fptr(c->o_Q[m]);
+        p.ldpre = c->ld[m];
+        if (m < L) {
+            p.aux = c->fptr(c->o_ZS[m]);
+            p.ldaux = c->ld[m];
+        }
+        const int tile = pick_tile(g, true);
+        ProfScope ps(c, KC_GEMM_ROP);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 3. back-propagation with seed J^i v (the factor 2 of B = 2I goes into the final scale):
+    //    delta^L = Q^L,  delta^{m-1} = (delta^m (W^m)^T) * sigma'(s^{m-1})  ->  T^{m-1}
+    for (int m = L; m >= 2; --m) {
+        GemmGroup g;
+        g.nprob = 1;
+        GemmProblem& p = g.p[0];
+        const float* delta = m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]);
+        p = mk_problem(delta, c->ld[m], c->fptr(c->o_WT) + c->woff[m], c->dims[m], c->fptr(c->o_T[m - 1]), c->ld[m - 1], s,
+                       c->dims[m - 1], c->dims[m]);
+        p.aux = c->fptr(c->o_ZS[m - 1]);
+        p.ldaux = c->ld[m - 1];
+        const int tile = pick_tile(g, true);
+        ProfScope ps(c, KC_GEMM_ROP);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 4. sums over samples for every layer, then out = v/C + (2/|S|) * sums
+    TnPlan pl = plan_tn(c, s, true, 0);
+    if (pl.total > c->tn_floats) return DN_ENOSPC;
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            GemmProblem& p = g.p[m - 1];
+            p = mk_problem(m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]),
+                           c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
+            p.b_ones_col = 1;
+            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+        }
+        ProfScope ps(c, KC_GEMM_TN_MATVEC);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    return tn_reduce(c, &pl, false, v, out, 2.0 / (double)s);
 }
 
 int dn_profile_enable(dn_ctx* c, int on) {

@@ -73,6 +73,7 @@ def test_call_order_and_argument_errors(lib):
     assert lib.dn_jacobian_prep(h, fake, fake, 100, fake, 11) == -1                  # s > s_max
     assert lib.dn_gn_matvec(h, fake, fake, 0) == -3                                  # no Jacobian prepared
     assert lib.dn_gn_matvec(h, fake, fake, 5) == -1
+    assert lib.dn_gn_matvec_rop(h, fake, fake) == -3 and lib.dn_gn_matvec_rop(h, None, fake) == -1
     assert lib.dn_cg(h, fake, 1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -3
     assert lib.dn_cg(h, fake, -1.0, 0.0, 5, 0, fake, ctypes.byref(it), ctypes.byref(f)) == -1
     assert lib.dn_cg_sync(h, fake, 1.0, 1e-3, 5, 1, 0, 50.0, fake, ctypes.byref(it), ctypes.byref(f)) == -3

@@ -38,6 +38,12 @@ def _check_products(w, modes=(dn.DN_FULL, dn.DN_BLOCKDIAG)):
         again = w.empty()
         dn.dn_gn_matvec(w.ctx, dv, again, mode)
         assert torch.equal(out, again)
+        if mode == dn.DN_FULL:
+            # the same product without the stored blocks (forward-mode pass + back-propagation)
+            dn.dn_gn_matvec_rop(w.ctx, dv, again)
+            err = rel_l2(again.cpu().numpy(), ref)
+            print(f"[{w.cfg.name}] without stored blocks: rel err {err:.2e}", flush=True)
+            assert err <= TOL
 
 
 def _check_grad(w):

@@ -215,3 +215,16 @@ def test_paper_initialisations(init):
         dn.dn_gn_matvec(w.ctx, w.dev(v), out, mode)
         assert rel_l2(out.cpu().numpy(), w.oracle_matvec(v, blockdiag=(mode == dn.DN_BLOCKDIAG))) <= TOL
     w.ctx.close()
+
+
+def test_product_without_stored_blocks(wl):
+    """dn_gn_matvec_rop (forward-mode pass + back-propagation, no stored blocks) gives the same G^S v as the oracle
+    and as the product from the stored blocks: two independent device paths to one result."""
+    dn.dn_jacobian_prep(wl.ctx, wl.dtheta, wl.dX, wl.dS)
+    v = dn_inputs.make_probe(wl.cfg, 1)
+    a, b = wl.empty(), wl.empty()
+    dn.dn_gn_matvec_rop(wl.ctx, wl.dev(v), a)
+    dn.dn_gn_matvec(wl.ctx, wl.dev(v), b, dn.DN_FULL)
+    ref = wl.oracle_matvec(v)
+    assert rel_l2(a.cpu().numpy(), ref) <= TOL
+    assert rel_l2(a.cpu().numpy(), b.cpu().numpy()) <= TOL
