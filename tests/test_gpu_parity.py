@@ -228,3 +228,25 @@ def test_product_without_stored_blocks(wl):
     ref = wl.oracle_matvec(v)
     assert rel_l2(a.cpu().numpy(), ref) <= TOL
     assert rel_l2(a.cpu().numpy(), b.cpu().numpy()) <= TOL
+
+
+def test_subsample_edge_cases():
+    """Repeated row ids count twice (the product is a plain sum over the list), a subsample of one row, the
+    subsample equal to all rows, and s below s_max after a larger one (the workspace keeps no stale rows)."""
+    cfg = dn_inputs.custom((7, 5, 6, 3), l=40, s=40, C=2.0, seed=12)
+    X, Y = dn_inputs.make_X(cfg), dn_inputs.make_Y(cfg)
+    theta = dn_inputs.make_theta(cfg, bias_scale=0.3)
+    dev = "cuda:0"
+    dX, dth = torch.from_numpy(X).to(dev), torch.from_numpy(theta).to(dev)
+    ctx = dn.Context(cfg.dims, cfg.C, cfg.l, cfg.s)
+    v = dn_inputs.make_probe(cfg, 0)
+    dv = torch.from_numpy(v).to(dev)
+    out = torch.empty(ctx.n, dtype=torch.float32, device=dev)
+    th64, X64 = theta.astype(np.float64), X.astype(np.float64)
+    for S in (np.arange(40), np.array([3, 3, 3, 17, 17, 0]), np.array([39]), np.array([5, 9, 5])):
+        S = S.astype(np.int32)
+        dn.dn_jacobian_prep(ctx, dth, dX, torch.from_numpy(S).to(dev))
+        for mode, fn in ((dn.DN_FULL, orc.gn_matvec), (dn.DN_BLOCKDIAG, orc.gn_matvec_blockdiag)):
+            dn.dn_gn_matvec(ctx, dv, out, mode)
+            assert rel_l2(out.cpu().numpy(), fn(th64, cfg.dims, cfg.C, X64[S], v.astype(np.float64))) <= TOL
+    ctx.close()
