@@ -5,7 +5,7 @@
 #include <stdint.h>
 
 #define DN_MAX_LAYERS 8
-#define DN_MAX_WSLOTS 16
+#define DN_MAX_WSLOTS 32
 #define DN_MAX_PARTIALS 1024
 #define DN_MAX_SPLIT 4                                  // neuron groups per layer of a split structure
 #define DN_MAX_SEGS (DN_MAX_LAYERS * DN_MAX_SPLIT * DN_MAX_SPLIT)   // independent CG systems (partitions)
@@ -297,47 +297,58 @@ __global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int c
 // this kernel is slower than streaming it):
 // one work-group per sample, wave w keeps the 4-column strips of P^m_i (all n_L rows) in
 // registers, so every stored element is read from HBM exactly once per product.
-template <int NLMAX>
+template <int NLMAX, int CH>
 __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) {
+    // wave w owns strip slots w, w + waves, ... (CH of them at most); a slot is 256 columns of one layer
     __shared__ float part[DN_MAX_WSLOTS][NLMAX];
     __shared__ float rb[DN_MAX_LAYERS][NLMAX];
     const int i = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int m = a.wlayer[wave];
-    const int j = 4 * (64 * a.wcol[wave] + lane);
-    const bool live = j < a.n[m];
-    float4 p[NLMAX];
-    float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float* __restrict__ pbase = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
-    if (live) q4 = *reinterpret_cast<const float4*>(a.Q[m] + (long long)i * a.ld[m] + j);
-    if (live && a.Qb[m]) {
-        const float4 qb = *reinterpret_cast<const float4*>(a.Qb[m] + (long long)i * a.ld[m] + j);
-        q4.x += qb.x; q4.y += qb.y; q4.z += qb.z; q4.w += qb.w;
-    }
-    // padding columns of Q are never written; mask them
-    if (live) {
-        const int rem = a.n[m] - j;
-        if (rem < 4) { q4.w = 0.f; if (rem < 3) q4.z = 0.f; if (rem < 2) q4.y = 0.f; }
-    }
+    const int nwaves = blockDim.x >> 6;
+    int m[CH], j[CH];
+    bool live[CH];
+    float4 p[CH][NLMAX];
+    float4 q4[CH];
 #pragma unroll
-    for (int u = 0; u < NLMAX; ++u) {
-        p[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (live && u < a.nL) p[u] = *reinterpret_cast<const float4*>(pbase + (long long)u * a.ld[m]);
-    }
-    // columns past n_m hold padding: keep them out of the sums
-    if (live) {
-        const int rem = a.n[m] - j;
-        if (rem < 4) {
+    for (int ch = 0; ch < CH; ++ch) {
+        const int slot = wave + ch * nwaves;
+        const bool have = slot < a.nwslots;
+        m[ch] = have ? a.wlayer[slot] : 1;
+        j[ch] = have ? 4 * (64 * a.wcol[slot] + lane) : 0;
+        live[ch] = have && j[ch] < a.n[m[ch]];
+        const long long ldm = a.ld[m[ch]];
+        q4[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live[ch]) q4[ch] = *reinterpret_cast<const float4*>(a.Q[m[ch]] + (long long)i * ldm + j[ch]);
+        if (live[ch] && a.Qb[m[ch]]) {
+            const float4 qb = *reinterpret_cast<const float4*>(a.Qb[m[ch]] + (long long)i * ldm + j[ch]);
+            q4[ch].x += qb.x; q4[ch].y += qb.y; q4[ch].z += qb.z; q4[ch].w += qb.w;
+        }
+        const float* __restrict__ pbase = a.P[m[ch]] + (long long)i * a.nL * ldm + j[ch];
 #pragma unroll
-            for (int u = 0; u < NLMAX; ++u) { p[u].w = 0.f; if (rem < 3) p[u].z = 0.f; if (rem < 2) p[u].y = 0.f; }
+        for (int u = 0; u < NLMAX; ++u) {
+            p[ch][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (live[ch] && u < a.nL) p[ch][u] = *reinterpret_cast<const float4*>(pbase + (long long)u * ldm);
         }
     }
 #pragma unroll
-    for (int u = 0; u < NLMAX; ++u) {
-        if (u < a.nL) {
-            float x = p[u].x * q4.x + p[u].y * q4.y + p[u].z * q4.z + p[u].w * q4.w;
-            x = wave_sum(x);
-            if (lane == 0) part[wave][u] = x;
+    for (int ch = 0; ch < CH; ++ch) {
+        // columns past n_m hold padding (never written): keep them out of the sums
+        const int rem = live[ch] ? a.n[m[ch]] - j[ch] : 4;
+        if (rem < 4) {
+            q4[ch].w = 0.f; if (rem < 3) q4[ch].z = 0.f; if (rem < 2) q4[ch].y = 0.f;
+#pragma unroll
+            for (int u = 0; u < NLMAX; ++u) {
+                p[ch][u].w = 0.f; if (rem < 3) p[ch][u].z = 0.f; if (rem < 2) p[ch][u].y = 0.f;
+            }
+        }
+        const int slot = wave + ch * nwaves;
+#pragma unroll
+        for (int u = 0; u < NLMAX; ++u) {
+            if (u < a.nL) {
+                float x = p[ch][u].x * q4[ch].x + p[ch][u].y * q4[ch].y + p[ch][u].z * q4[ch].z + p[ch][u].w * q4[ch].w;
+                x = wave_sum(x);
+                if (lane == 0 && slot < a.nwslots) part[slot][u] = x;
+            }
         }
     }
     __syncthreads();
@@ -368,17 +379,20 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
         }
     }
     __syncthreads();
-    if (live) {
-        const float* rr = a.blockdiag ? rb[m] : rb[0];
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < NLMAX; ++u) {
-            if (u < a.nL) {
-                const float w = rr[u];
-                acc.x += p[u].x * w; acc.y += p[u].y * w; acc.z += p[u].z * w; acc.w += p[u].w * w;
+    for (int ch = 0; ch < CH; ++ch) {
+        if (live[ch]) {
+            const float* rr = a.blockdiag ? rb[m[ch]] : rb[0];
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < NLMAX; ++u) {
+                if (u < a.nL) {
+                    const float w = rr[u];
+                    acc.x += p[ch][u].x * w; acc.y += p[ch][u].y * w; acc.z += p[ch][u].z * w; acc.w += p[ch][u].w * w;
+                }
             }
+            *reinterpret_cast<float4*>(a.T[m[ch]] + (long long)i * a.ld[m[ch]] + j[ch]) = acc;
         }
-        *reinterpret_cast<float4*>(a.T[m] + (long long)i * a.ld[m] + j) = acc;
     }
 }
 

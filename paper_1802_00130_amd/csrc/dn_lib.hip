@@ -621,7 +621,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
     StreamArgs a;
     fill_stream_args(c, a, mode);
-    const bool fused = L >= 2 && nL <= 16 && a.nwslots <= DN_MAX_WSLOTS;
+    const bool fused = L >= 2 && ((nL <= 16 && a.nwslots <= 16) || (nL <= 12 && a.nwslots <= DN_MAX_WSLOTS));
     const bool bd = mode == DN_BLOCKDIAG;
     // 1. inner sums over t for every layer: Q^m = Z^{m-1} V^m + vb^m.  On the two-pass path the
     //    last hidden layer's result is scaled by sigma'(s^{L-1}) on the way out (it is only ever used
@@ -644,8 +644,8 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         // in.  The launch then consists of tiles of similar length (measured at 784-300-300-10, |S| = 3000:
         // 30.2 -> 26.8 us).
         if (fused && tile == 64 && L < DN_MAX_GROUP && group_tiles(g, 64, 64) <= 3 * c->num_cus) {
-            int big = 0;
-            for (int k = 1; k < L; ++k)
+            int big = 0;                       // among the hidden layers: Q^L is read as it is
+            for (int k = 1; k + 1 < L; ++k)
                 if (g.p[k].K > g.p[big].K) big = k;
             int other = 0;
             for (int k = 0; k < L; ++k)
@@ -671,11 +671,20 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
     if (fused) {
         ProfScope ps(c, KC_JV_JTV_FUSED);
         DN_HIP(c, ps.err);
-        const dim3 grid(s), block(64 * a.nwslots);
-        if (nL <= 4)       hipLaunchKernelGGL(jv_jtv_fused_kernel<4>, grid, block, 0, c->stream, a);
-        else if (nL <= 8)  hipLaunchKernelGGL(jv_jtv_fused_kernel<8>, grid, block, 0, c->stream, a);
-        else if (nL <= 12) hipLaunchKernelGGL(jv_jtv_fused_kernel<12>, grid, block, 0, c->stream, a);
-        else               hipLaunchKernelGGL(jv_jtv_fused_kernel<16>, grid, block, 0, c->stream, a);
+        // up to 16 waves per work-group; with more than 16 strip slots (hidden widths above 4096 in total)
+        // every wave keeps two strips, which the register budget allows for n_L <= 12
+        const int waves = std::min(a.nwslots, 16);
+        const dim3 grid(s), block(64 * waves);
+        if (a.nwslots <= 16) {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_kernel<4, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_kernel<8, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_kernel<12, 1>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_kernel<16, 1>), grid, block, 0, c->stream, a);
+        } else {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_kernel<4, 2>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_kernel<8, 2>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_kernel<12, 2>), grid, block, 0, c->stream, a);
+        }
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     } else {

@@ -250,3 +250,35 @@ def test_subsample_edge_cases():
             dn.dn_gn_matvec(ctx, dv, out, mode)
             assert rel_l2(out.cpu().numpy(), fn(th64, cfg.dims, cfg.C, X64[S], v.astype(np.float64))) <= TOL
     ctx.close()
+
+
+WIDE = {
+    # n_L <= 12, hidden widths 4096 < total <= 8192: the fused kernel with two strips per wave
+    "fused2_16-2500-2100-10": lambda: dn_inputs.custom((16, 2500, 2100, 10), l=40, s=12, C=4.0, seed=81),
+    "fused2_12-4100-3": lambda: dn_inputs.custom((12, 4100, 3), l=30, s=9, C=2.0, seed=82),
+    # n_L <= 16 but too wide for the fused kernel: the two-pass kernels with a small output layer
+    "twopass_small_nL_8-5000-4000-6": lambda: dn_inputs.custom((8, 5000, 4000, 6), l=30, s=8, C=3.0, seed=83),
+    "twopass_small_nL_10-8500-5": lambda: dn_inputs.custom((10, 8500, 5), l=30, s=8, C=3.0, seed=84),
+    # 12 < n_L <= 16 with more than 4096 hidden columns: no fused variant, two-pass
+    "twopass_nL14_9-3000-1500-14": lambda: dn_inputs.custom((9, 3000, 1500, 14), l=30, s=8, C=3.0, seed=85),
+}
+
+
+@pytest.mark.parametrize("name", sorted(WIDE))
+def test_wide_hidden_layers_small_output(name):
+    print(f"[case] {name}", flush=True)
+    w = Workload(WIDE[name](), bias_scale=0.3)
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    v = dn_inputs.make_probe(w.cfg, 0)
+    out = w.empty()
+    w.ctx.profile_enable(True)
+    w.ctx.profile_reset()
+    for mode in (dn.DN_FULL, dn.DN_BLOCKDIAG):
+        dn.dn_gn_matvec(w.ctx, w.dev(v), out, mode)
+        err = rel_l2(out.cpu().numpy(), w.oracle_matvec(v, blockdiag=(mode == dn.DN_BLOCKDIAG)))
+        print(f"  mode {mode}: rel err {err:.2e}", flush=True)
+        assert err <= TOL
+    prof = w.ctx.profile_read()
+    assert (prof["jv_jtv_fused"][1] == 2) == name.startswith("fused2")
+    assert (prof["jv_rows"][1] == 2) == name.startswith("twopass")
+    w.ctx.close()
