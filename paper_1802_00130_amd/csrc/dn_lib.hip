@@ -857,15 +857,43 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         const int rc = flush();
         if (rc != DN_OK) return rc;
     }
-    // 2. the two passes over the stored blocks
-    if (L >= 2) {
-        ProfScope ps(c, KC_JV);
+    // 2. the passes over the stored blocks: one pass when a sample's strips fit one work-group's registers
+    //    (as in the other modes), else the general two-pass kernels
+    {
+        int w = 0;
+        for (int m = 1; m < L; ++m)
+            for (int cidx = 0; cidx < cdiv(c->dims[m], 256); ++cidx, ++w)
+                if (w < DN_MAX_WSLOTS) {
+                    a.wlayer[w] = m;
+                    a.wcol[w] = cidx;
+                }
+        a.nwslots = w;
+    }
+    const bool fused = L >= 2 && c->stream_passes != 2 &&
+                       ((nL <= 16 && a.nwslots <= 16) || (nL <= 8 && a.nwslots <= DN_MAX_WSLOTS));
+    if (fused) {
+        ProfScope ps(c, KC_JV_JTV_FUSED);
         DN_HIP(c, ps.err);
-        hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 4)), dim3(256), 0, c->stream, a);
+        const dim3 grid(s), block(64 * std::min(a.nwslots, 16));
+        if (a.nwslots <= 16) {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_part_kernel<12, 1>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<16, 1>), grid, block, 0, c->stream, a);
+        } else {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 2>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 2>), grid, block, 0, c->stream, a);
+        }
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
-    }
-    {
+    } else {
+        if (L >= 2) {
+            ProfScope ps(c, KC_JV);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 4)), dim3(256), 0, c->stream, a);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
         ProfScope ps(c, KC_JTV);
         DN_HIP(c, ps.err);
         int chunks = 1;

@@ -25,6 +25,8 @@ CASES = {
     "wide_out_1-2-1-3": (lambda: dn_inputs.custom((24, 40, 36, 50), l=100, s=30, C=4.0, seed=76), (1, 2, 1, 3)),
     "five_layers": (lambda: dn_inputs.custom((10, 9, 8, 7, 6, 3), l=100, s=50, C=3.0, seed=77), (2, 2, 1, 2, 2, 1)),
     "mid_1-2-2-1": (lambda: dn_inputs.custom((200, 300, 260, 10), l=900, s=300, C=50.0, seed=78), (1, 2, 2, 1)),
+    # more than 16 strip slots: two strips per wave in the single-pass kernel
+    "wide_2-3-4-1": (lambda: dn_inputs.custom((14, 2600, 1700, 7), l=40, s=10, C=4.0, seed=79), (2, 3, 4, 1)),
 }
 
 
@@ -41,11 +43,15 @@ def test_partitioned_product_and_cg(name):
     out = w.empty()
     for k in range(2):
         v = dn_inputs.make_probe(cfg, k)
-        dn.dn_gn_matvec(w.ctx, w.dev(v), out, dn.DN_PARTITION)
         ref = orc.gn_matvec_partitioned(th64, cfg.dims, cfg.C, w.XS64, v.astype(np.float64), split)
-        err = rel_l2(out.cpu().numpy(), ref)
-        print(f"  product {k}: rel err {err:.2e}", flush=True)
-        assert err <= 1e-4
+        for passes in (0, 2):        # single-pass kernel where there is one, and the general two-pass kernels
+            w.ctx.set_stream_passes(passes)
+            out.fill_(float("nan"))
+            dn.dn_gn_matvec(w.ctx, w.dev(v), out, dn.DN_PARTITION)
+            err = rel_l2(out.cpu().numpy(), ref)
+            print(f"  product {k}, passes {passes}: rel err {err:.2e}", flush=True)
+            assert err <= 1e-4
+    w.ctx.set_stream_passes(0)
     # the other modes are untouched by a split structure
     dn.dn_gn_matvec(w.ctx, w.dev(v), out, dn.DN_BLOCKDIAG)
     assert rel_l2(out.cpu().numpy(), w.oracle_matvec(v, blockdiag=True)) <= 1e-4
