@@ -12,12 +12,6 @@
 
 namespace dn {
 
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
-
 // DPP lane permutation inside rows of 16 lanes (no LDS traffic); CTRL as in the ISA:
 // 0xB1 = quad_perm [1,0,3,2], 0x4E = quad_perm [2,3,0,1], 0x141 = row_half_mirror, 0x140 = row_mirror.
 template <int CTRL>
@@ -346,8 +340,8 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
         for (int u = 0; u < NLMAX; ++u) {
             if (u < a.nL) {
                 float x = p[ch][u].x * q4[ch].x + p[ch][u].y * q4[ch].y + p[ch][u].z * q4[ch].z + p[ch][u].w * q4[ch].w;
-                x = wave_sum(x);
-                if (lane == 0 && slot < a.nwslots) part[slot][u] = x;
+                x = wave_sum_to_lane63(x);
+                if (lane == 63 && slot < a.nwslots) part[slot][u] = x;
             }
         }
     }
