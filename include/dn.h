@@ -214,7 +214,8 @@ int dn_newton_step(dn_ctx* ctx, float* theta, const float* X, const float* Y, in
  * forgets it.  With mode DN_PARTITION dn_gn_matvec applies the diagonal blocks of G^S over these
  * partitions, dn_cg / dn_cg_sync solve the independent systems (resnorm_host then has
  * dn_num_partitions entries), dn_newton_step uses them in its CG.  All groups[m] = 1 is DN_BLOCKDIAG.
- * The products of this mode use general two-pass kernels (every hidden layer's block is streamed twice).
+ * With n_L <= 16 the stored blocks are read once per product as in the other modes; wider outputs use general
+ * two-pass kernels (every hidden layer's block is streamed twice).
  */
 int dn_set_split(dn_ctx* ctx, const int* groups);
 int dn_num_partitions(const dn_ctx* ctx);

@@ -848,7 +848,8 @@ __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const
 // from input group a to output group b (and, for a = 0, the biases of group b).  For each input group a the
 // inner sums over t in that group are Q^{m,a} (one dense product each); per partition
 //   r^{(a,b)}_i[u] = sum_{j in group b} P^m_i[u][j] q^{m,a,i}_j,     t^{m,a,i}_j = sum_u P^m_i[u][j] 2 r^{(a,b(j))}_i[u].
-// These two kernels are the general (two-pass) form; all hidden layers' blocks are streamed.
+// jv_part_kernel / jtv_part_kernel are the general (two-pass) form, jv_jtv_fused_part_kernel the single-pass
+// one for small outputs; all hidden layers' blocks are streamed.
 struct PartArgs {
     int L, s, nL;
     int n[DN_MAX_LAYERS + 1];

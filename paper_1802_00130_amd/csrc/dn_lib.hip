@@ -809,7 +809,7 @@ void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
 
 bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG && mode != DN_PARTITION; }
 
-// Product over the partitions of the split structure (Section 3.1, 4.1), general two-pass form
+// Product over the partitions of the split structure (Section 3.1, Section 4.1)
 int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
     PartArgs a;
