@@ -201,6 +201,16 @@ def main():
     prof = ctx.profile_read()
     ctx.profile_enable(False)
 
+    # what an EMPTY event bracket reads on this stream while it is busy: the part of avg_kernel_ms that is
+    # not kernel time (a profiler's per-dispatch duration does not contain it)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(32)]
+    for a, b in pairs:
+        dn.dn_gn_matvec(ctx, dv, out, dn.DN_FULL)
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    bracket_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+
     phase_ms = {p: 0.0 for p in phases}
     for evs in events:
         for i, p in enumerate(phases):
@@ -222,7 +232,7 @@ def main():
         peak, unit = PEAK_HBM_GBS, "GB/s"
     roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
                 "frac": achieved / peak, "traffic": measured_traffic(cfg.name, dominant), "avg_kernel_ms": avg_ms, "launches": int(launches),
-                "work_per_launch": unit_work}
+                "work_per_launch": unit_work, "empty_event_bracket_ms": bracket_ms}
 
     mv_tflops = matvec_flops(cfg, cfg.s) / (mv_ms * 1e-3) / 1e12
     res = {
