@@ -749,6 +749,17 @@ __device__ __forceinline__ void cg_locate(const CgSegs& sg, int& seg, long long&
     if (hi > sg.off[seg + 1]) hi = sg.off[seg + 1];
 }
 
+// Elements [lo, hi) of a chunk: groups of four through 16-byte accesses (fv; the vectors carry no alignment
+// beyond that of a float: segments start anywhere in theta), the last hi - lo mod 4 one by one (fs).
+template <class FV, class FS>
+__device__ __forceinline__ void cg_sweep(long long lo, long long hi, FV fv, FS fs) {
+    const long long tail = lo + ((hi - lo) & ~3LL);
+    for (long long e = lo + 4 * (long long)threadIdx.x; e < tail; e += 1024) fv(e);
+    if (tail + threadIdx.x < hi) fs(tail + threadIdx.x);
+}
+__device__ __forceinline__ f32x4v ld4(const float* p) { return *reinterpret_cast<const f32x4v*>(p); }
+__device__ __forceinline__ void st4(float* p, f32x4v v) { *reinterpret_cast<f32x4v*>(p) = v; }
+
 // d = 0, r = p = -g, partial g^T g
 __global__ __launch_bounds__(256) void cg_init_kernel(const CgSegs sg, const float* __restrict__ g,
                                                       float* __restrict__ d, float* __restrict__ r,
@@ -757,11 +768,19 @@ __global__ __launch_bounds__(256) void cg_init_kernel(const CgSegs sg, const flo
     int seg; long long lo, hi;
     cg_locate(sg, seg, lo, hi);
     double acc = 0.0;
-    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
-        const float ge = g[e];
-        d[e] = 0.f; r[e] = -ge; p[e] = -ge;
-        acc += (double)ge * (double)ge;
-    }
+    cg_sweep(lo, hi,
+             [&](long long e) {
+                 const f32x4v ge = ld4(g + e);
+                 const f32x4v z = {0.f, 0.f, 0.f, 0.f};
+                 st4(d + e, z); st4(r + e, -ge); st4(p + e, -ge);
+                 acc += ((double)ge[0] * (double)ge[0] + (double)ge[1] * (double)ge[1]) +
+                        ((double)ge[2] * (double)ge[2] + (double)ge[3] * (double)ge[3]);
+             },
+             [&](long long e) {
+                 const float ge = g[e];
+                 d[e] = 0.f; r[e] = -ge; p[e] = -ge;
+                 acc += (double)ge * (double)ge;
+             });
     acc = block_sum_d(acc, red);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
@@ -786,10 +805,18 @@ __global__ __launch_bounds__(256) void cg_dot_kernel(const CgSegs sg, const floa
     int seg; long long lo, hi;
     cg_locate(sg, seg, lo, hi);
     double acc = 0.0;
-    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
-        const float pe = p[e];
-        acc += (double)pe * (double)(q[e] + lambda * pe);
-    }
+    cg_sweep(lo, hi,
+             [&](long long e) {
+                 const f32x4v pe = ld4(p + e), qe = ld4(q + e);
+                 double s4[4];
+#pragma unroll
+                 for (int k = 0; k < 4; ++k) s4[k] = (double)pe[k] * (double)(qe[k] + lambda * pe[k]);
+                 acc += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+             },
+             [&](long long e) {
+                 const float pe = p[e];
+                 acc += (double)pe * (double)(q[e] + lambda * pe);
+             });
     acc = block_sum_d(acc, red);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
@@ -810,13 +837,27 @@ __global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, cons
     const double pq = block_sum_range(pq_partials, sg.cb[seg], sg.cb[seg + 1], red);
     const float alpha = (float)(st->rho[seg] / pq);
     double acc = 0.0;
-    for (long long e = lo + threadIdx.x; e < hi; e += 256) {
-        const float pe = p[e];
-        d[e] += alpha * pe;
-        const float re = r[e] - alpha * (q[e] + lambda * pe);
-        r[e] = re;
-        acc += (double)re * (double)re;
-    }
+    cg_sweep(lo, hi,
+             [&](long long e) {
+                 const f32x4v pe = ld4(p + e), qe = ld4(q + e);
+                 f32x4v de = ld4(d + e), re = ld4(r + e);
+                 double s4[4];
+#pragma unroll
+                 for (int k = 0; k < 4; ++k) {
+                     de[k] += alpha * pe[k];
+                     re[k] = re[k] - alpha * (qe[k] + lambda * pe[k]);
+                     s4[k] = (double)re[k] * (double)re[k];
+                 }
+                 st4(d + e, de); st4(r + e, re);
+                 acc += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+             },
+             [&](long long e) {
+                 const float pe = p[e];
+                 d[e] += alpha * pe;
+                 const float re = r[e] - alpha * (q[e] + lambda * pe);
+                 r[e] = re;
+                 acc += (double)re * (double)re;
+             });
     acc = block_sum_d(acc, red);
     if (threadIdx.x == 0) rr_partials[blockIdx.x] = acc;
 }
@@ -839,7 +880,15 @@ __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const
     if (first) { st_next->rho[seg] = rho_new; st_next->active[seg] = stop ? 0 : 1; }
     if (stop) return;
     const float beta = (float)(rho_new / st_cur->rho[seg]);
-    for (long long e = lo + threadIdx.x; e < hi; e += 256) p[e] = r[e] + beta * p[e];
+    cg_sweep(lo, hi,
+             [&](long long e) {
+                 const f32x4v re = ld4(r + e);
+                 f32x4v pe = ld4(p + e);
+#pragma unroll
+                 for (int k = 0; k < 4; ++k) pe[k] = re[k] + beta * pe[k];
+                 st4(p + e, pe);
+             },
+             [&](long long e) { p[e] = r[e] + beta * p[e]; });
 }
 
 // ---------------------------------------------------------------------------------------------

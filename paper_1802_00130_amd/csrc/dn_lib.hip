@@ -790,8 +790,9 @@ void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
         sg.off[0] = 0;
         sg.off[1] = c->n;
     }
-    // chunk size: at most ~512 work-groups in total, at least 2048 elements each
-    long long chunk = std::max<long long>(2048, round_up((c->n + 511) / 512, 1024));
+    // chunk size: about 768 work-groups in total (3 per CU; every segment adds at most one more), at least
+    // 2048 elements each
+    long long chunk = std::max<long long>(2048, round_up((c->n + 767) / 768, 1024));
     for (;;) {
         long long tot = 0;
         for (int k = 0; k < sg.nseg; ++k) tot += (sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk;
