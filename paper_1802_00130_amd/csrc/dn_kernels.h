@@ -72,18 +72,33 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restric
 // ---------------------------------------------------------------------------------------------
 // First stored block (Section 3.3, recursion started from dz^L/dz^L = I):
 //   P^{L-1}_i[u][j] = w^L_{ju} * sigma'(s^{L-1,i}_j),   sigma' = z(1-z).
-// AL is the n_L x n_{L-1} slice of theta for layer L.
+// AL is the padded copy of the n_L x n_{L-1} slice of theta for layer L.
 __global__ __launch_bounds__(256) void jac_init_kernel(const float* __restrict__ AL, const float* __restrict__ Z,
-                                                       float* __restrict__ P, int s, int nL, int nh, long long ldz,
-                                                       long long ldp) {
-    const long long total = (long long)s * nL * nh;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
-        const int j = (int)(e % nh);
-        const long long iu = e / nh;
-        const int u = (int)(iu % nL);
-        const long long i = iu / nL;
-        const float z = Z[i * ldz + j];
-        P[iu * ldp + j] = AL[(long long)u * nh + j] * (z * (1.0f - z));
+                                                       float* __restrict__ P, int s, int nL, int nh, long long ld) {
+    // AL, Z and P share the padded row length ld (a multiple of 4, rows 16-byte aligned); blockIdx.y walks the
+    // samples, the x dimension the n_L x ld/4 groups of four columns of one sample
+    const int ld4 = (int)(ld >> 2);
+    const int total4 = nL * ld4;
+    for (int i = blockIdx.y; i < s; i += gridDim.y) {
+        const float* __restrict__ z = Z + (long long)i * ld;
+        float* __restrict__ Pi = P + (long long)i * nL * ld;
+        for (int e = blockIdx.x * 256 + threadIdx.x; e < total4; e += gridDim.x * 256) {
+            const int u = e / ld4;
+            const int j = 4 * (e - u * ld4);
+            if (j >= nh) continue;                       // padding columns are never written
+            const float4 a4 = *reinterpret_cast<const float4*>(AL + (long long)u * ld + j);
+            const float4 z4 = *reinterpret_cast<const float4*>(z + j);
+            const float4 o = make_float4(a4.x * (z4.x * (1.0f - z4.x)), a4.y * (z4.y * (1.0f - z4.y)),
+                                         a4.z * (z4.z * (1.0f - z4.z)), a4.w * (z4.w * (1.0f - z4.w)));
+            float* dst = Pi + (long long)u * ld + j;
+            if (j + 3 < nh) {
+                *reinterpret_cast<float4*>(dst) = o;
+            } else {
+                dst[0] = o.x;
+                if (j + 1 < nh) dst[1] = o.y;
+                if (j + 2 < nh) dst[2] = o.z;
+            }
+        }
     }
 }
 

@@ -1167,9 +1167,9 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_for((long long)nL * c->dims[L - 1])), dim3(256), 0, c->stream,
                            theta + c->woff[L], c->fptr(c->o_AL), (long long)nL, c->dims[L - 1], c->ld[L - 1]);
         DN_HIP(c, hipGetLastError());
-        hipLaunchKernelGGL(jac_init_kernel, dim3(grid_for((long long)s * nL * c->dims[L - 1])), dim3(256), 0,
-                           c->stream, theta + c->woff[L], c->fptr(c->o_ZS[L - 1]), c->fptr(c->o_P[L - 1]), s, nL,
-                           c->dims[L - 1], c->ld[L - 1], c->ld[L - 1]);
+        const dim3 jgrid(std::min(64, grid_for((long long)nL * c->ld[L - 1] / 4, 256)), std::min(s, 32768));
+        hipLaunchKernelGGL(jac_init_kernel, jgrid, dim3(256), 0, c->stream, c->fptr(c->o_AL),
+                           c->fptr(c->o_ZS[L - 1]), c->fptr(c->o_P[L - 1]), s, nL, c->dims[L - 1], c->ld[L - 1]);
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     }
