@@ -1,0 +1,132 @@
+// Launch plumbing of the GEMM engine: problem descriptors, tile walk, tile and K-slice choices.
+// Part of the one translation unit dn_lib.hip (helpers live in its unnamed namespace).
+#pragma once
+#include "dn_host_ctx.h"
+
+namespace {
+
+// ---- GEMM plumbing -----------------------------------------------------------------------
+
+GemmProblem mk_problem(const float* A, long long lda, const float* B, long long ldb, float* Cc, long long ldc, int M,
+                       int N, int K) {
+    GemmProblem p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = A; p.B = B; p.C = Cc;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.M = M; p.N = N; p.K = K;
+    p.auxdiv = 1;
+    p.alpha = 1.0f;
+    p.splits = 1;
+    p.k_per_split = K;
+    return p;
+}
+
+// Fill tile counts and the tile walk.  splits applies to every problem of the group.
+void finalize_group(GemmGroup& g, int BM, int BN, int BK, int splits) {
+    int begin = 0;
+    for (int i = 0; i < g.nprob; ++i) {
+        GemmProblem& p = g.p[i];
+        p.tiles_m = cdiv(p.M, BM);
+        p.tiles_n = cdiv(p.N, BN);
+        p.splits = splits;
+        p.k_per_split = (int)round_up(cdiv(p.K, splits), BK);
+        p.tile_begin = begin;
+        begin += p.tiles_m * p.tiles_n;
+    }
+    g.tiles_per_split = begin;
+    g.total_tiles = begin * splits;
+    g.group_m = kGroupM;
+    g.grid = g.total_tiles;
+    if (splits > 1 || g.nprob == 1) {
+        g.xcd_mode = XCD_RANGES;
+    } else {
+        g.xcd_mode = XCD_PER_PROBLEM;
+        int most = 0;
+        for (int x = 0; x < kXcds; ++x) {
+            int mine = 0;
+            for (int i = 0; i < g.nprob; ++i) {
+                const int tiles = g.p[i].tiles_m * g.p[i].tiles_n;
+                mine += tiles / kXcds + (x < tiles % kXcds ? 1 : 0);
+            }
+            most = std::max(most, mine);
+        }
+        g.grid = kXcds * most;
+    }
+}
+
+int group_tiles(const GemmGroup& g, int BM, int BN) {
+    int t = 0;
+    for (int i = 0; i < g.nprob; ++i) t += cdiv(g.p[i].M, BM) * cdiv(g.p[i].N, BN);
+    return t;
+}
+
+template <int BM, int BN, int BK, int PF, int LA, int LB, int CLS, bool PIN = false>
+hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, 2, 2, LA, LB, PF, PIN, CLS>), dim3(g.grid), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+// Tile variants (measured on MI355X):
+//   128x128, K-tile 16, 2 tiles in flight             large products of K-contiguous operands (>= 1024 tiles)
+//   64x64,   K-tile 16, 4 in flight, pinned schedule  launches of <= 4 work-groups per CU, and sums over samples
+//   64x64,   K-tile 16, 4 in flight                   everything else
+template <int LA, int LB, int CLS>
+hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
+    if (tile == 128) {
+        finalize_group(g, 128, 128, 16, splits);
+        return launch_gemm_t<128, 128, 16, 2, LA, LB, CLS>(g, st);
+    }
+    finalize_group(g, 64, 64, 16, splits);
+    // the hand-placed schedule wins for small launches, and at every size when both operands go through
+    // the transposing loads (sums over samples)
+    if (g.total_tiles <= 4 * 256 || (LA == RT && LB == RT)) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
+    return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS>(g, st);
+}
+
+// Measured on MI355X: 64x64 tiles win on every shape of the path except products with both operands
+// K-contiguous and both output dimensions >= 1024, where 128x128 tiles are ~5% faster once there are
+// >= 4 of them per CU.
+int pick_tile(const GemmGroup& g, bool both_k_contiguous) {
+    if (!both_k_contiguous || group_tiles(g, 128, 128) < 1024) return 64;
+    for (int i = 0; i < g.nprob; ++i)
+        if (g.p[i].M < 1024 || g.p[i].N < 1024) return 64;
+    return 128;
+}
+
+// K-slices of a sum over samples: enough to give every CU about 4 work-groups, at least 256 samples per
+// slice.  From 6 slices on the count is rounded to a multiple of 8: the tile walk hands each XCD a
+// contiguous eighth of the launch, and with 8 k slices that is exactly k whole slices, read once into that
+// XCD's L2 (measured at 784-300-300-10, |S| = 3000: 10 slices 37.3 us, 8 slices 33.0 us, 16 slices 36.9 us).
+int pick_splits(int tiles, int K) {
+    int s = std::max(1, kTargetWGs / std::max(1, tiles));
+    s = std::min(s, std::max(1, K / 256));
+    s = std::min(s, 64);
+    if (s >= 6) s = std::max(8, (s + 4) / 8 * 8);
+    return s;
+}
+
+// Plan of the sums over samples  W_m = T^m^T [Z^{m-1}, 1]  for K samples.  grouped: all layers in
+// one launch (product); otherwise one launch per layer (gradient).
+TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
+    TnPlan pl;
+    std::memset(&pl, 0, sizeof(pl));
+    int tiles = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        if (!grouped && m != only_layer) continue;
+        tiles += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
+    }
+    pl.tile = 64;
+    pl.splits = pick_splits(tiles, K);
+    pl.k_per_split = (int)round_up(cdiv(K, pl.splits), kBKmax);
+    long long off = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        pl.offset[m] = off;
+        pl.floats[m] = (long long)pl.splits * c->dims[m] * c->ldw[m];
+        off += round_up(pl.floats[m], 64);
+    }
+    pl.total = off;
+    return pl;
+}
+
+}  // namespace

@@ -1,0 +1,555 @@
+// Forward pass, objective, and the Gauss-Newton products (all block modes) as sequences of launches.
+// Part of the one translation unit dn_lib.hip (helpers live in its unnamed namespace).
+#pragma once
+#include "dn_host_workspace.h"
+
+namespace {
+
+// ---- forward pass on `rows` rows: Zin -> Z[1..upto] ---------------------------------------
+int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0, int rows, const size_t* o_Z,
+                   int upto) {
+    const float* zin = Z0;
+    long long ldin = ld0;
+    for (int m = 1; m <= upto; ++m) {
+        GemmGroup g;
+        g.nprob = 1;
+        float* zout = c->fptr(o_Z[m]);
+        g.p[0] = mk_problem(zin, ldin, theta + c->woff[m], c->dims[m - 1], zout, c->ld[m], rows, c->dims[m],
+                            c->dims[m - 1]);
+        g.p[0].bias = theta + c->boff[m];
+        const int tile = pick_tile(g, true);
+        ProfScope ps(c, KC_GEMM_FWD);
+        DN_HIP(c, ps.err);
+        g.p[0].sigmoid = m < c->L ? 1 : 0;
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_FWD>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+        zin = zout;
+        ldin = c->ld[m];
+    }
+    return DN_OK;
+}
+
+// objective from Z^L of all rows; optionally writes the gradient seed 2(z^L - y)
+// Loss terms of the `rows` samples whose outputs are in Z^L of the workspace (one chunk of the l samples);
+// optionally the gradient seed 2(z^L - y) and a dense copy of z^L.  first: this is the first chunk (the
+// partial sums start from zero).  last && f_host: add the regularisation term and return f.
+int objective(dn_ctx* c, const float* theta, const float* Y, int rows, int l, bool first, bool last, float* delta,
+              long long ldd, float* zl_out, double* f_host) {
+    const int L = c->L;
+    // the grid of the first (largest) chunk defines how many partial sums there are
+    const int nb_all = std::min(DN_MAX_PARTIALS, grid_for((long long)std::min(l, c->l_max) * c->dims[L]));
+    const int nb_loss = std::min(nb_all, grid_for((long long)rows * c->dims[L]));
+    const int nb_reg = std::min(DN_MAX_PARTIALS, grid_for(c->n));
+    ProfScope ps(c, KC_LOSS);
+    DN_HIP(c, ps.err);
+    hipLaunchKernelGGL(loss_delta_kernel, dim3(nb_loss), dim3(256), 0, c->stream, c->fptr(c->o_Zall[L]), c->ld[L], Y,
+                       rows, c->dims[L], delta, ldd, zl_out, c->dptr(c->o_part[0]), first ? 0 : 1);
+    DN_HIP(c, hipGetLastError());
+    if (f_host && last) {
+        hipLaunchKernelGGL(sumsq_kernel, dim3(nb_reg), dim3(256), 0, c->stream, theta, c->n, c->dptr(c->o_part[1]));
+        DN_HIP(c, hipGetLastError());
+        hipLaunchKernelGGL(objective_finalize_kernel, dim3(1), dim3(256), 0, c->stream, c->dptr(c->o_part[0]),
+                           nb_all, c->dptr(c->o_part[1]), nb_reg, 1.0 / (2.0 * c->C), 1.0 / (double)l,
+                           c->dptr(c->o_f));
+        DN_HIP(c, hipGetLastError());
+    }
+    DN_HIP(c, ps.end());
+    if (f_host && last) {
+        DN_HIP(c, hipMemcpyAsync(f_host, c->dptr(c->o_f), sizeof(double), hipMemcpyDeviceToHost, c->stream));
+        DN_HIP(c, hipStreamSynchronize(c->stream));
+    }
+    return DN_OK;
+}
+
+// out = x/C + scale * (folded partial sums), theta layout
+int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan for all */, bool per_layer,
+              const float* x, float* out, double scale) {
+    ReduceArgs ra;
+    std::memset(&ra, 0, sizeof(ra));
+    ra.L = c->L;
+    for (int m = 0; m <= c->L; ++m) ra.n[m] = c->dims[m];
+    int blocks = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        const TnPlan& pl = per_layer ? plans[m] : plans[0];
+        ra.off[m] = c->woff[m];
+        ra.W[m] = c->fptr(c->o_tn) + pl.offset[m];
+        ra.ldw[m] = c->ldw[m];
+        ra.split_stride[m] = (long long)c->dims[m] * c->ldw[m];
+        ra.splits[m] = pl.splits;
+        ra.chunks[m] = cdiv(c->dims[m - 1] + 1, 1024);
+        ra.blk_begin[m] = blocks;
+        blocks += c->dims[m] * ra.chunks[m];
+    }
+    ra.blk_begin[c->L + 1] = blocks;
+    ProfScope ps(c, KC_TN_REDUCE);
+    DN_HIP(c, ps.err);
+    hipLaunchKernelGGL(tn_reduce_kernel, dim3(blocks), dim3(256), 0, c->stream, ra, x, out, (float)(1.0 / c->C),
+                       (float)scale);
+    DN_HIP(c, hipGetLastError());
+    DN_HIP(c, ps.end());
+    return DN_OK;
+}
+
+void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
+    std::memset(&a, 0, sizeof(a));
+    a.L = c->L;
+    a.s = c->s_cur;
+    a.nL = c->dims[c->L];
+    a.blockdiag = mode == DN_BLOCKDIAG ? 1 : 0;
+    for (int m = 0; m <= c->L; ++m) {
+        a.n[m] = c->dims[m];
+        a.ld[m] = c->ld[m];
+    }
+    for (int m = 1; m < c->L; ++m) a.P[m] = c->fptr(c->o_P[m]);
+    for (int m = 1; m <= c->L; ++m) {
+        a.Q[m] = c->fptr(c->o_Q[m]);
+        a.T[m] = c->fptr(c->o_T[m]);
+    }
+    a.R = c->fptr(c->o_R);
+    a.ldr = c->ldr;
+    int w = 0;
+    for (int m = 1; m < c->L; ++m)
+        for (int cidx = 0; cidx < cdiv(c->dims[m], 256); ++cidx, ++w)
+            if (w < DN_MAX_WSLOTS) {
+                a.wlayer[w] = m;
+                a.wcol[w] = cidx;
+            }
+    a.nwslots = w;
+}
+
+// ---- team kernel plumbing ------------------------------------------------------------------
+struct TeamPlan {
+    bool ok = false;
+    TeamArgs ta;
+};
+
+hipError_t plan_team(dn_ctx* c, const StreamArgs& a, TeamPlan& tp) {
+    tp.ok = false;
+    const int L = c->L;
+    if (c->stream_passes == 2 || c->team_rpt == 0) return hipSuccess;
+    if (c->team_wgs_per_cu == 0) {
+        int nb = 0;
+        hipError_t e = c->team_rpt == 16
+                           ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<16, 0, 4>, 256, 0)
+                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<32, 8, 3>, 256, 0);
+        if (e != hipSuccess) return e;
+        c->team_wgs_per_cu = nb >= 1 ? nb : -1;
+    }
+    if (c->team_wgs_per_cu < 1) return hipSuccess;
+    TeamArgs& ta = tp.ta;
+    std::memset(&ta, 0, sizeof(ta));
+    ta.a = a;
+    const int RB = 4 * c->team_rpt;
+    int ncs = 0;
+    for (int m = 1; m + 1 < L; ++m) {
+        ta.slice_begin[m] = ncs;
+        ncs += cdiv(c->dims[m], 256);
+    }
+    const int G = c->team_nrs * ncs;
+    const int resident = std::min(kMaxResidentWGs, c->num_cus * c->team_wgs_per_cu);
+    const int teams = std::min(a.s, resident / G);
+    if (teams < 1) return hipSuccess;
+    ta.G = G;
+    ta.teams = teams;
+    ta.nrs = c->team_nrs;
+    ta.ncs = ncs;
+    ta.ntasks = (RB / 32) * ta.nrs * (a.blockdiag ? (L - 2) : 1);
+    ta.nfolders = std::min(G, ta.ntasks);
+    ta.part = reinterpret_cast<unsigned long long*>(c->ws + c->o_texch);
+    ta.rbar = ta.part + kTeamExchWords;
+    for (int m = 1; m + 1 < L; ++m) ta.tpart[m] = c->team_nrs > 1 ? c->fptr(c->o_ttp[m]) : nullptr;
+    ta.error = reinterpret_cast<unsigned*>(c->ws + c->o_terr);
+    ta.spin_limit = c->spin_limit;
+    tp.ok = true;
+    return hipSuccess;
+}
+
+hipError_t launch_team(dn_ctx* c, TeamPlan& tp) {
+    TeamArgs& ta = tp.ta;
+    const unsigned per_launch = (unsigned)cdiv(ta.a.s, ta.teams) + 1u;
+    if (!c->team_clean || c->team_seq > 0x7fff0000u) {
+        // first use after dn_bind (or the sequence numbers are about to wrap): start from a blank slate
+        hipLaunchKernelGGL(team_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ta.part, 2 * kTeamExchWords,
+                           ta.error);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        c->team_clean = true;
+        c->team_seq = 0;
+    }
+    ta.seq_base = c->team_seq;
+    c->team_seq += per_launch;
+    c->team_used = true;
+    const dim3 grid(ta.teams * ta.G), block(256);
+    if (c->team_rpt == 16) hipLaunchKernelGGL((jv_jtv_team_kernel<16, 0, 4>), grid, block, 0, c->stream, ta);
+    else                   hipLaunchKernelGGL((jv_jtv_team_kernel<32, 8, 3>), grid, block, 0, c->stream, ta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || ta.nrs == 1) return e;
+    // several row slices: add their partial transposed products
+    for (int m = 1; m + 1 < c->L; ++m) {
+        const long long total4 = (long long)ta.a.s * c->ld[m] / 4;
+        hipLaunchKernelGGL(team_fold_t_kernel, dim3(grid_for(total4, 256 * 4)), dim3(256), 0, c->stream, ta.tpart[m],
+                           c->fptr(c->o_T[m]), ta.nrs, total4);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// after a synchronisation: has a wait of the team kernel run out?
+int team_status(dn_ctx* c) {
+    if (!c->team_used) return DN_OK;
+    unsigned err = 0;
+    DN_HIP(c, hipMemcpyAsync(&err, c->ws + c->o_terr, sizeof(err), hipMemcpyDeviceToHost, c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    return err ? DN_ETIMEOUT : DN_OK;
+}
+
+int gn_matvec_part(dn_ctx* c, const float* v, float* out);
+
+// out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
+int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
+    if (mode == DN_PARTITION) return c->split_set ? gn_matvec_part(c, v, out) : DN_ESTATE;
+    const int L = c->L, s = c->s_cur, nL = c->dims[L];
+    StreamArgs a;
+    fill_stream_args(c, a, mode);
+    const bool fused = L >= 2 && ((nL <= 16 && a.nwslots <= 16) || (nL <= 12 && a.nwslots <= DN_MAX_WSLOTS));
+    const bool bd = mode == DN_BLOCKDIAG;
+    // 1. inner sums over t for every layer: Q^m = Z^{m-1} V^m + vb^m.  On the two-pass path the
+    //    last hidden layer's result is scaled by sigma'(s^{L-1}) on the way out (it is only ever used
+    //    as A^L (sigma' * q^{L-1})).
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            g.p[m - 1] = mk_problem(c->fptr(c->o_ZS[m - 1]), c->ld[m - 1], v + c->woff[m], c->dims[m - 1],
+                                    c->fptr(c->o_Q[m]), c->ld[m], s, c->dims[m], c->dims[m - 1]);
+            g.p[m - 1].bias = v + c->boff[m];
+            if (!fused && L >= 2 && m == L - 1) {
+                g.p[m - 1].aux = c->fptr(c->o_ZS[L - 1]);
+                g.p[m - 1].ldaux = c->ld[L - 1];
+            }
+        }
+        const int tile = pick_tile(g, true);
+        // Small launches (a few tiles per CU) whose longest sum over t is at least twice any other: cut that
+        // layer's sum in two halves, written to Q^m and a second buffer that the fused kernel adds on the way
+        // in.  The launch then consists of tiles of similar length (measured at 784-300-300-10, |S| = 3000:
+        // 30.2 -> 26.8 us).
+        if (fused && tile == 64 && L < DN_MAX_GROUP && group_tiles(g, 64, 64) <= 3 * c->num_cus) {
+            int big = 0;                       // among the hidden layers: Q^L is read as it is
+            for (int k = 1; k + 1 < L; ++k)
+                if (g.p[k].K > g.p[big].K) big = k;
+            int other = 0;
+            for (int k = 0; k < L; ++k)
+                if (k != big) other = std::max(other, g.p[k].K);
+            if (g.p[big].K >= 512 && g.p[big].K >= 2 * other) {
+                const int kh = (int)round_up(g.p[big].K / 2, 16);
+                GemmProblem& second = g.p[g.nprob++];
+                second = g.p[big];
+                second.A += kh;
+                second.B += kh;
+                second.K -= kh;
+                second.C = c->fptr(c->o_Qb);
+                second.bias = nullptr;
+                g.p[big].K = kh;
+                a.Qb[big + 1] = c->fptr(c->o_Qb);
+            }
+        }
+        ProfScope ps(c, KC_GEMM_Q);
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, tile, 1, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 2. the two passes over the Jacobian blocks
+    if (fused) {
+        ProfScope ps(c, KC_JV_JTV_FUSED);
+        DN_HIP(c, ps.err);
+        // up to 16 waves per work-group; with more than 16 strip slots (hidden widths above 4096 in total)
+        // every wave keeps two strips, which the register budget allows for n_L <= 12
+        const int waves = std::min(a.nwslots, 16);
+        const dim3 grid(s), block(64 * waves);
+        if (a.nwslots <= 16) {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_kernel<4, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_kernel<8, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_kernel<12, 1>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_kernel<16, 1>), grid, block, 0, c->stream, a);
+        } else {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_kernel<4, 2>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_kernel<8, 2>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_kernel<12, 2>), grid, block, 0, c->stream, a);
+        }
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    } else {
+        const long long slab = (long long)s * c->ldr;   // one layer's rows of R
+        if (L >= 2) {
+            // block L-1 applied as a dense product:  (sigma' * q^{L-1}) A^L^T, added to q^L (full) or
+            // kept as r^{L-1} (per-layer)
+            GemmGroup g;
+            g.nprob = 1;
+            GemmProblem& p = g.p[0];
+            float* dst = bd ? c->fptr(c->o_R) + (long long)(L - 2) * slab : c->fptr(c->o_Q[L]);
+            const long long lddst = bd ? c->ldr : c->ld[L];
+            p = mk_problem(c->fptr(c->o_Q[L - 1]), c->ld[L - 1], c->fptr(c->o_AL), c->ld[L - 1], dst, lddst, s, nL,
+                           c->dims[L - 1]);
+            if (!bd) {
+                p.add = dst;
+                p.ldadd = lddst;
+            }
+            ProfScope ps(c, KC_GEMM_IMPLICIT);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
+            DN_HIP(c, ps.end());
+        }
+        TeamPlan tp;
+        DN_HIP(c, plan_team(c, a, tp));
+        if (tp.ok) {
+            // one read of the stored blocks: teams of work-groups, see jv_jtv_team_kernel
+            ProfScope ps(c, KC_JV_JTV_TEAM);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, launch_team(c, tp));
+            DN_HIP(c, ps.end());
+        } else {
+            {
+                ProfScope ps(c, KC_JV);
+                DN_HIP(c, ps.err);
+                constexpr int UB = 16;
+                hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a);
+                DN_HIP(c, hipGetLastError());
+                DN_HIP(c, ps.end());
+            }
+            {
+                ProfScope ps(c, KC_JTV);
+                DN_HIP(c, ps.err);
+                int chunks = 1;
+                for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
+                hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
+                                   sizeof(float) * nL, c->stream, a, chunks);
+                DN_HIP(c, hipGetLastError());
+                DN_HIP(c, ps.end());
+            }
+        }
+        if (L >= 2) {
+            // t^{L-1} = sigma' * (A^L^T 2r):  T^L already holds 2r (full); per-layer uses 2 r^{L-1}
+            GemmGroup g;
+            g.nprob = 1;
+            GemmProblem& p = g.p[0];
+            const float* src = bd ? c->fptr(c->o_R) + (long long)(L - 2) * slab : c->fptr(c->o_T[L]);
+            const long long ldsrc = bd ? c->ldr : c->ld[L];
+            p = mk_problem(src, ldsrc, c->fptr(c->o_AL), c->ld[L - 1], c->fptr(c->o_T[L - 1]), c->ld[L - 1], s,
+                           c->dims[L - 1], nL);
+            p.aux = c->fptr(c->o_ZS[L - 1]);
+            p.ldaux = c->ld[L - 1];
+            p.alpha = bd ? 2.0f : 1.0f;
+            ProfScope ps(c, KC_GEMM_IMPLICIT);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
+            DN_HIP(c, ps.end());
+        }
+    }
+    // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1]
+    TnPlan pl = plan_tn(c, s, true, 0);
+    if (pl.total > c->tn_floats) return DN_ENOSPC;
+    {
+        GemmGroup g;
+        g.nprob = L;
+        for (int m = 1; m <= L; ++m) {
+            GemmProblem& p = g.p[m - 1];
+            p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]), c->ld[m - 1],
+                           c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
+            p.b_ones_col = 1;
+            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+        }
+        ProfScope ps(c, KC_GEMM_TN_MATVEC);
+        DN_HIP(c, ps.err);
+        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, ps.end());
+    }
+    // 4. fold slices, scale by 1/|S|, add v/C
+    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s);
+}
+
+void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
+    std::memset(&sg, 0, sizeof(sg));
+    if (mode == DN_PARTITION) {
+        sg.nseg = c->nparts;
+        for (int k = 0; k <= c->nparts; ++k) sg.off[k] = c->part_off[k];
+    } else if (mode == DN_BLOCKDIAG) {
+        sg.nseg = c->L;
+        for (int m = 1; m <= c->L; ++m) sg.off[m - 1] = c->woff[m];
+        sg.off[c->L] = c->n;
+    } else {
+        sg.nseg = 1;
+        sg.off[0] = 0;
+        sg.off[1] = c->n;
+    }
+    // chunk size: about 768 work-groups in total (3 per CU; every segment adds at most one more), at least
+    // 2048 elements each
+    long long chunk = std::max<long long>(2048, round_up((c->n + 767) / 768, 1024));
+    for (;;) {
+        long long tot = 0;
+        for (int k = 0; k < sg.nseg; ++k) tot += (sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk;
+        if (tot <= DN_MAX_PARTIALS) break;
+        chunk *= 2;
+    }
+    sg.chunk = (int)chunk;
+    int b = 0;
+    for (int k = 0; k < sg.nseg; ++k) {
+        sg.cb[k] = b;
+        b += (int)((sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk);
+    }
+    sg.cb[sg.nseg] = b;
+}
+
+bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG && mode != DN_PARTITION; }
+
+// Product over the partitions of the split structure (Section 3.1, Section 4.1)
+int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
+    const int L = c->L, s = c->s_cur, nL = c->dims[L];
+    PartArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.L = L; a.s = s; a.nL = nL;
+    for (int m = 0; m <= L; ++m) {
+        a.n[m] = c->dims[m];
+        a.ld[m] = c->ld[m];
+        a.split[m] = c->split[m];
+        for (int k = 0; k <= DN_MAX_SPLIT; ++k) a.bound[m][k] = c->gbound[m][k];
+    }
+    for (int m = 1; m <= L + 1; ++m) a.part_base[m] = c->part_base[m];
+    for (int m = 1; m < L; ++m) a.P[m] = c->fptr(c->o_P[m]);
+    for (int m = 1; m <= L; ++m) {
+        a.Qp[m] = c->fptr(c->o_Qp[m]);
+        a.Tp[m] = c->fptr(c->o_Tp[m]);
+    }
+    a.R = c->fptr(c->o_Rp);
+    a.ldr = c->ldr;
+    // 1. inner sums over t, one product per (layer, input group); the bias term rides with group 0
+    {
+        GemmGroup g;
+        g.nprob = 0;
+        auto flush = [&]() -> int {
+            if (g.nprob == 0) return DN_OK;
+            ProfScope ps(c, KC_GEMM_Q);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 64, 1, c->stream)));
+            DN_HIP(c, ps.end());
+            g.nprob = 0;
+            return DN_OK;
+        };
+        for (int m = 1; m <= L; ++m)
+            for (int x = 0; x < c->split[m - 1]; ++x) {
+                const int t0 = c->gbound[m - 1][x], t1 = c->gbound[m - 1][x + 1];
+                GemmProblem& p = g.p[g.nprob++];
+                p = mk_problem(c->fptr(c->o_ZS[m - 1]) + t0, c->ld[m - 1], v + c->woff[m] + t0, c->dims[m - 1],
+                               c->fptr(c->o_Qp[m]) + (long long)x * s * c->ld[m], c->ld[m], s, c->dims[m], t1 - t0);
+                if (x == 0) p.bias = v + c->boff[m];
+                if (g.nprob == DN_MAX_GROUP) {
+                    const int rc = flush();
+                    if (rc != DN_OK) return rc;
+                }
+            }
+        const int rc = flush();
+        if (rc != DN_OK) return rc;
+    }
+    // 2. the passes over the stored blocks: one pass when a sample's strips fit one work-group's registers
+    //    (as in the other modes), else the general two-pass kernels
+    {
+        int w = 0;
+        for (int m = 1; m < L; ++m)
+            for (int cidx = 0; cidx < cdiv(c->dims[m], 256); ++cidx, ++w)
+                if (w < DN_MAX_WSLOTS) {
+                    a.wlayer[w] = m;
+                    a.wcol[w] = cidx;
+                }
+        a.nwslots = w;
+    }
+    const bool fused = L >= 2 && c->stream_passes != 2 &&
+                       ((nL <= 16 && a.nwslots <= 16) || (nL <= 8 && a.nwslots <= DN_MAX_WSLOTS));
+    if (fused) {
+        ProfScope ps(c, KC_JV_JTV_FUSED);
+        DN_HIP(c, ps.err);
+        const dim3 grid(s), block(64 * std::min(a.nwslots, 16));
+        if (a.nwslots <= 16) {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 1>), grid, block, 0, c->stream, a);
+            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_part_kernel<12, 1>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<16, 1>), grid, block, 0, c->stream, a);
+        } else {
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 2>), grid, block, 0, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 2>), grid, block, 0, c->stream, a);
+        }
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    } else {
+        if (L >= 2) {
+            ProfScope ps(c, KC_JV);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 4)), dim3(256), 0, c->stream, a);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
+        ProfScope ps(c, KC_JTV);
+        DN_HIP(c, ps.err);
+        int chunks = 1;
+        for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 256);
+        int most = 1;
+        for (int m = 1; m < L; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
+        const size_t lds = sizeof(float) * (size_t)most * nL;
+        hipLaunchKernelGGL(jtv_part_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256), lds, c->stream, a,
+                           chunks);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // 3. sums over samples, one product per (layer, input group) into that group's columns; bias sums apart
+    TnPlan pl = plan_tn(c, s, true, 0);
+    if (pl.total > c->tn_floats) return DN_ENOSPC;
+    {
+        GemmGroup g;
+        g.nprob = 0;
+        auto flush = [&]() -> int {
+            if (g.nprob == 0) return DN_OK;
+            ProfScope ps(c, KC_GEMM_TN_MATVEC);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+            DN_HIP(c, ps.end());
+            g.nprob = 0;
+            return DN_OK;
+        };
+        for (int m = 1; m <= L; ++m)
+            for (int x = 0; x < c->split[m - 1]; ++x) {
+                const int t0 = c->gbound[m - 1][x], t1 = c->gbound[m - 1][x + 1];
+                GemmProblem& p = g.p[g.nprob++];
+                p = mk_problem(c->fptr(c->o_Tp[m]) + (long long)x * s * c->ld[m], c->ld[m], c->fptr(c->o_ZS[m - 1]) + t0,
+                               c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m] + t0, c->ldw[m], c->dims[m], t1 - t0, s);
+                p.split_stride = (long long)c->dims[m] * c->ldw[m];
+                if (g.nprob == DN_MAX_GROUP) {
+                    const int rc = flush();
+                    if (rc != DN_OK) return rc;
+                }
+            }
+        const int rc = flush();
+        if (rc != DN_OK) return rc;
+        BiasSumArgs ba;
+        std::memset(&ba, 0, sizeof(ba));
+        ba.L = L; ba.s = s; ba.splits = pl.splits;
+        // the K-slices are those of the products above (finalize_group: slice length rounded up to the K tile)
+        ba.k_per_split = (int)round_up(cdiv(s, pl.splits), 16);
+        int chunks = 0;
+        for (int m = 0; m <= L; ++m) { ba.n[m] = c->dims[m]; ba.ld[m] = c->ld[m]; }
+        for (int m = 1; m <= L; ++m) {
+            ba.T0[m] = c->fptr(c->o_Tp[m]);
+            ba.W[m] = c->fptr(c->o_tn) + pl.offset[m];
+            ba.ldw[m] = c->ldw[m];
+            ba.first[m] = chunks;
+            chunks += cdiv(c->dims[m], 16);
+        }
+        ba.first[L + 1] = chunks;
+        ProfScope ps(c, KC_TN_REDUCE);
+        DN_HIP(c, ps.err);
+        hipLaunchKernelGGL(bias_colsum_kernel, dim3(chunks * pl.splits), dim3(256), 0, c->stream, ba);
+        DN_HIP(c, hipGetLastError());
+        DN_HIP(c, ps.end());
+    }
+    // 4. fold slices, scale by 1/|S|, add v/C
+    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s);
+}
+
+}  // namespace

@@ -1,0 +1,317 @@
+// Block-diagonal product for a general split structure (variable partitions of Section 3.1).
+#pragma once
+#include "dn_common.h"
+
+namespace dn {
+
+// ---------------------------------------------------------------------------------------------
+// Block-diagonal product for a general split structure (variable partitions of Section 3.1; Section 4.1).
+// Layer m has ga = split[m-1] input groups and gb = split[m] output groups; partition (a, b) owns the weights
+// from input group a to output group b (and, for a = 0, the biases of group b).  For each input group a the
+// inner sums over t in that group are Q^{m,a} (one dense product each); per partition
+//   r^{(a,b)}_i[u] = sum_{j in group b} P^m_i[u][j] q^{m,a,i}_j,     t^{m,a,i}_j = sum_u P^m_i[u][j] 2 r^{(a,b(j))}_i[u].
+// jv_part_kernel / jtv_part_kernel are the general (two-pass) form, jv_jtv_fused_part_kernel the single-pass
+// one for small outputs; all hidden layers' blocks are streamed.
+struct PartArgs {
+    int L, s, nL;
+    int n[DN_MAX_LAYERS + 1];
+    long long ld[DN_MAX_LAYERS + 1];
+    int split[DN_MAX_LAYERS + 1];
+    int bound[DN_MAX_LAYERS + 1][DN_MAX_SPLIT + 1];   // bound[m][k]: first neuron of group k of layer m
+    int part_base[DN_MAX_LAYERS + 2];                 // first partition id of layer m (1..L)
+    const float* P[DN_MAX_LAYERS + 1];                // P[m], m = 1..L-1
+    const float* Qp[DN_MAX_LAYERS + 1];               // Q^{m,a}: Qp[m] + a * s * ld[m]
+    float* Tp[DN_MAX_LAYERS + 1];                     // T^{m,a}: Tp[m] + a * s * ld[m]
+    float* R;                                         // [partitions][s][ldr], hidden layers only
+    long long ldr;
+    // single-pass kernel: strip slot k is 256 columns of layer wlayer[k], starting at 256 * wcol[k]
+    int nwslots;
+    int wlayer[DN_MAX_WSLOTS];
+    int wcol[DN_MAX_WSLOTS];
+};
+
+__device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
+    int g = 0;
+#pragma unroll
+    for (int k = 1; k < DN_MAX_SPLIT; ++k)
+        if (k < groups && j >= bound[k]) g = k;
+    return g;
+}
+
+// work-group = (sample, block of 4 outputs); each wave takes one row u of every hidden layer's block
+__global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
+    constexpr int UB = 4;
+    const int ublocks = (a.nL + UB - 1) / UB;
+    const int i = blockIdx.x / ublocks;
+    const int u0 = (blockIdx.x - i * ublocks) * UB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long slab = (long long)a.s * a.ldr;
+    for (int uu = wave; uu < UB; uu += 4) {
+        const int u = u0 + uu;
+        if (u >= a.nL) break;
+        for (int m = 1; m < a.L; ++m) {
+            const int ga = a.split[m - 1], gb = a.split[m];
+            const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
+            double acc[DN_MAX_SPLIT][DN_MAX_SPLIT];
+#pragma unroll
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+#pragma unroll
+                for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] = 0.0;
+            // four columns at a time (rows are 16-byte aligned and padded to a multiple of 4 floats; the padding of
+            // P and Q holds no data, so the last, partial group of four is masked); a group boundary may fall
+            // inside a group of four, hence the per-column group index
+            const int nm4 = (a.n[m] + 3) >> 2;
+            for (int c4 = lane; c4 < nm4; c4 += 64) {
+                const int j = 4 * c4;
+                const float4 p4 = *reinterpret_cast<const float4*>(prow + j);
+                const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
+                int bj[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bj[e] = (j + e < a.n[m]) ? group_of(a.bound[m], gb, j + e) : -1;
+#pragma unroll
+                for (int x = 0; x < DN_MAX_SPLIT; ++x) {
+                    if (x < ga) {
+                        const float4 q4 = *reinterpret_cast<const float4*>(a.Qp[m] + ((long long)x * a.s + i) * a.ld[m] + j);
+                        const float qe[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const double t = bj[e] >= 0 ? (double)pe[e] * (double)qe[e] : 0.0;
+#pragma unroll
+                            for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] += (y == bj[e]) ? t : 0.0;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+#pragma unroll
+                for (int y = 0; y < DN_MAX_SPLIT; ++y) {
+                    if (x < ga && y < gb) {
+                        const double t = wave_sum_d(acc[x][y]);
+                        if (lane == 0)
+                            a.R[(long long)(a.part_base[m] + x * gb + y) * slab + (long long)i * a.ldr + u] = (float)t;
+                    }
+                }
+        }
+    }
+}
+
+// work-group = (sample, layer, chunk of 256 columns); one thread per column.  Layer L: t^{L,a} = 2 q^{L,a}.
+__global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chunks_total) {
+    extern __shared__ float rbar[];          // [ga][gb][nL] of this layer
+    const int i = blockIdx.x / chunks_total;
+    int c = blockIdx.x - i * chunks_total;
+    int m = 1;
+    for (; m < a.L; ++m) {
+        const int cm = (a.n[m] + 255) >> 8;
+        if (c < cm) break;
+        c -= cm;
+    }
+    const int ga = a.split[m - 1];
+    if (m == a.L) {
+        // identity block: groups of outputs stay apart by themselves
+        for (int x = 0; x < ga; ++x)
+            for (int u = threadIdx.x; u < a.nL; u += 256) {
+                const long long e = ((long long)x * a.s + i) * a.ld[m] + u;
+                a.Tp[m][e] = 2.0f * a.Qp[m][e];
+            }
+        return;
+    }
+    const int gb = a.split[m];
+    const long long slab = (long long)a.s * a.ldr;
+    for (int e = threadIdx.x; e < ga * gb * a.nL; e += 256) {
+        const int pl = e / a.nL, u = e - pl * a.nL;
+        rbar[e] = 2.0f * a.R[(long long)(a.part_base[m] + pl) * slab + (long long)i * a.ldr + u];
+    }
+    __syncthreads();
+    const int j = (c << 8) + threadIdx.x;
+    if (j >= a.n[m]) return;
+    const int bj = group_of(a.bound[m], gb, j);
+    const float* __restrict__ pcol = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
+    double acc[DN_MAX_SPLIT];
+#pragma unroll
+    for (int x = 0; x < DN_MAX_SPLIT; ++x) acc[x] = 0.0;
+#pragma unroll 4
+    for (int u = 0; u < a.nL; ++u) {
+        const double pj = (double)pcol[(long long)u * a.ld[m]];
+#pragma unroll
+        for (int x = 0; x < DN_MAX_SPLIT; ++x)
+            if (x < ga) acc[x] += pj * (double)rbar[(x * gb + bj) * a.nL + u];
+    }
+#pragma unroll
+    for (int x = 0; x < DN_MAX_SPLIT; ++x)
+        if (x < ga) a.Tp[m][((long long)x * a.s + i) * a.ld[m] + j] = (float)acc[x];
+}
+
+// Both passes in one for a split structure when n_L <= NLMAX and the hidden widths fit one work-group: the
+// strips of P^m_i stay in registers as in jv_jtv_fused_kernel; per input group x the partial sums are kept
+// apart by the output group of each column, and the transposed product picks, column by column, the r of
+// that column's partition.  One HBM read of the stored blocks per product.
+template <int NLMAX, int CH>
+__global__ __launch_bounds__(1024) void jv_jtv_fused_part_kernel(const PartArgs a) {
+    __shared__ float part[DN_MAX_WSLOTS][DN_MAX_SPLIT][NLMAX];          // [slot][output group][u], one x at a time
+    __shared__ float rb[DN_MAX_LAYERS][DN_MAX_SPLIT][NLMAX];            // [layer][output group][u], one x at a time
+    const int i = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nwaves = blockDim.x >> 6;
+    int m[CH], j[CH], bj[CH][4], ylo[CH], yhi[CH];
+    bool live[CH];
+    float4 p[CH][NLMAX];
+    int gamax = 1;
+    for (int mm = 1; mm < a.L; ++mm) gamax = max(gamax, a.split[mm - 1]);
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        const int slot = wave + ch * nwaves;
+        const bool have = slot < a.nwslots;
+        m[ch] = have ? a.wlayer[slot] : 1;
+        j[ch] = have ? 4 * (64 * a.wcol[slot] + lane) : 0;
+        live[ch] = have && j[ch] < a.n[m[ch]];
+        {
+            // output groups of the first and last column of this strip slot (same for all lanes)
+            const int c0 = have ? 256 * a.wcol[slot] : 0;
+            ylo[ch] = group_of(a.bound[m[ch]], a.split[m[ch]], c0);
+            yhi[ch] = group_of(a.bound[m[ch]], a.split[m[ch]], min(c0 + 255, a.n[m[ch]] - 1));
+        }
+        const long long ldm = a.ld[m[ch]];
+        const float* __restrict__ pbase = a.P[m[ch]] + (long long)i * a.nL * ldm + j[ch];
+#pragma unroll
+        for (int u = 0; u < NLMAX; ++u) {
+            p[ch][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (live[ch] && u < a.nL) p[ch][u] = *reinterpret_cast<const float4*>(pbase + (long long)u * ldm);
+        }
+        // output group of each of the four columns; -1 for padding columns (and their P values cleared)
+        const int rem = live[ch] ? a.n[m[ch]] - j[ch] : 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bj[ch][e] = e < rem ? group_of(a.bound[m[ch]], a.split[m[ch]], j[ch] + e) : -1;
+        if (rem < 4) {
+#pragma unroll
+            for (int u = 0; u < NLMAX; ++u) {
+                p[ch][u].w = 0.f; if (rem < 3) p[ch][u].z = 0.f; if (rem < 2) p[ch][u].y = 0.f; if (rem < 1) p[ch][u].x = 0.f;
+            }
+        }
+    }
+    // output layer (identity block): t^{L,x} = 2 q^{L,x}
+    for (int x = 0; x < a.split[a.L - 1]; ++x)
+        for (int u = threadIdx.x; u < a.nL; u += blockDim.x) {
+            const long long e = ((long long)x * a.s + i) * a.ld[a.L] + u;
+            a.Tp[a.L][e] = 2.0f * a.Qp[a.L][e];
+        }
+    for (int x = 0; x < gamax; ++x) {
+        // ---- partial sums of this input group, kept apart by output group -------------------------
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            const int slot = wave + ch * nwaves;
+            const bool on = live[ch] && x < a.split[m[ch] - 1];
+            float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (on) q4 = *reinterpret_cast<const float4*>(a.Qp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch]);
+            // padding columns of Q are never written
+            if (bj[ch][0] < 0) q4.x = 0.f;
+            if (bj[ch][1] < 0) q4.y = 0.f;
+            if (bj[ch][2] < 0) q4.z = 0.f;
+            if (bj[ch][3] < 0) q4.w = 0.f;
+#pragma unroll
+            for (int u = 0; u < NLMAX; ++u) {
+                if (u < a.nL) {
+                    const float t0 = p[ch][u].x * q4.x, t1 = p[ch][u].y * q4.y, t2 = p[ch][u].z * q4.z,
+                                t3 = p[ch][u].w * q4.w;
+#pragma unroll
+                    for (int y = 0; y < DN_MAX_SPLIT; ++y) {
+                        // only the output groups that this strip's 256 columns touch need a reduction (uniform
+                        // in the wave); the others get a plain zero
+                        float v = 0.f;
+                        if (y >= ylo[ch] && y <= yhi[ch]) {
+                            v = (bj[ch][0] == y ? t0 : 0.f) + (bj[ch][1] == y ? t1 : 0.f) +
+                                (bj[ch][2] == y ? t2 : 0.f) + (bj[ch][3] == y ? t3 : 0.f);
+                            v = wave_sum_to_lane63(v);
+                        }
+                        if (lane == 63 && slot < a.nwslots) part[slot][y][u] = v;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // ---- r of every partition (layer, x, y), doubled: B = 2I ----------------------------------
+        for (int e = threadIdx.x; e < (a.L - 1) * DN_MAX_SPLIT * NLMAX; e += blockDim.x) {
+            const int u = e % NLMAX, y = (e / NLMAX) % DN_MAX_SPLIT, mm = e / (NLMAX * DN_MAX_SPLIT) + 1;
+            float rsum = 0.f;
+            for (int w = 0; w < a.nwslots; ++w)
+                if (a.wlayer[w] == mm) rsum += part[w][y][u];
+            rb[mm][y][u] = 2.0f * rsum;
+        }
+        __syncthreads();
+        // ---- transposed product: column j takes the r of its own partition -------------------------
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            if (live[ch] && x < a.split[m[ch] - 1]) {
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                const int y0 = bj[ch][0];
+#pragma unroll
+                for (int u = 0; u < NLMAX; ++u) {
+                    if (u < a.nL) {
+                        const float w0 = rb[m[ch]][y0][u];
+                        const float w1 = bj[ch][1] == y0 ? w0 : (bj[ch][1] >= 0 ? rb[m[ch]][bj[ch][1]][u] : 0.f);
+                        const float w2 = bj[ch][2] == y0 ? w0 : (bj[ch][2] >= 0 ? rb[m[ch]][bj[ch][2]][u] : 0.f);
+                        const float w3 = bj[ch][3] == y0 ? w0 : (bj[ch][3] >= 0 ? rb[m[ch]][bj[ch][3]][u] : 0.f);
+                        acc.x += p[ch][u].x * w0; acc.y += p[ch][u].y * w1; acc.z += p[ch][u].z * w2; acc.w += p[ch][u].w * w3;
+                    }
+                }
+                *reinterpret_cast<float4*>(a.Tp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch]) = acc;
+            }
+        }
+        // part and rb are rewritten for the next input group only after the barrier at the top of its second
+        // stage has been passed by everyone, i.e. after all reads above have been issued and completed
+        __syncthreads();
+    }
+}
+
+// bias part of the sums over samples for a split structure: the biases of layer m belong to the partitions of
+// input group 0, so their sums are the column sums of T^{m,0}.  K-slice k of the samples puts its sum into
+// column n_{m-1} of slice k of the partial buffer, where the products with a column of ones put theirs in
+// the other modes.  Work-group = (layer, 16 neurons, K-slice); 16 threads per neuron share the samples.
+struct BiasSumArgs {
+    int L, s;
+    int n[DN_MAX_LAYERS + 1];
+    long long ld[DN_MAX_LAYERS + 1];
+    const float* T0[DN_MAX_LAYERS + 1];     // T^{m,0}
+    float* W[DN_MAX_LAYERS + 1];            // partial buffer of layer m: [splits][n_m][ldw]
+    long long ldw[DN_MAX_LAYERS + 1];
+    int splits, k_per_split;
+    int first[DN_MAX_LAYERS + 2];           // first 16-neuron chunk of layer m
+};
+
+__global__ __launch_bounds__(256) void bias_colsum_kernel(const BiasSumArgs a) {
+    __shared__ double red[16][17];
+    const int chunk = blockIdx.x / a.splits, sidx = blockIdx.x - chunk * a.splits;
+    int m = 1;
+    for (int k = 2; k <= a.L; ++k)
+        if (chunk >= a.first[k]) m = k;
+    const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
+    const int j = (chunk - a.first[m]) * 16 + c;
+    const int i_lo = sidx * a.k_per_split, i_hi = min(a.s, i_lo + a.k_per_split);
+    double acc = 0.0;
+    if (j < a.n[m])
+        for (int i = i_lo + r; i < i_hi; i += 16) acc += (double)a.T0[m][(long long)i * a.ld[m] + j];
+    red[r][c] = acc;
+    __syncthreads();
+    if (r == 0 && j < a.n[m]) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += red[k][c];
+        a.W[m][(long long)sidx * a.n[m] * a.ldw[m] + (long long)j * a.ldw[m] + a.n[m - 1]] = (float)t;
+    }
+}
+
+// dst[k] = src[perm[k]]  (gather)  /  dst[perm[k]] = src[k]  (scatter);  perm lists the theta indices
+// partition by partition, so that every partition is contiguous in the gathered order
+__global__ __launch_bounds__(256) void perm_gather_kernel(const float* __restrict__ src, const int* __restrict__ perm,
+                                                          float* __restrict__ dst, long long n, float scale) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256)
+        dst[e] = scale * src[perm[e]];
+}
+__global__ __launch_bounds__(256) void perm_scatter_kernel(const float* __restrict__ src, const int* __restrict__ perm,
+                                                           float* __restrict__ dst, long long n) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)gridDim.x * 256)
+        dst[perm[e]] = src[e];
+}
+
+}  // namespace dn
