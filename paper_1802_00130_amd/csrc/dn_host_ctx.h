@@ -21,7 +21,6 @@ using namespace dn;
 
 namespace {
 
-constexpr int kTargetWGs = 1024;  // ~4 work-groups per compute unit (256 CUs)
 // K-tile depths; slices of split sums are cut at multiples of the deepest
 constexpr int kBKmax = 32;
 // tile rows per super-row of the tile walk: 8 x 8 tiles are about what one XCD (32 CUs) holds at a time

@@ -94,16 +94,29 @@ int pick_tile(const GemmGroup& g, bool both_k_contiguous) {
     return 128;
 }
 
-// K-slices of a sum over samples: enough to give every CU about 4 work-groups, at least 256 samples per
-// slice.  From 6 slices on the count is rounded to a multiple of 8: the tile walk hands each XCD a
-// contiguous eighth of the launch, and with 8 k slices that is exactly k whole slices, read once into that
-// XCD's L2 (measured at 784-300-300-10, |S| = 3000: 10 slices 37.3 us, 8 slices 33.0 us, 16 slices 36.9 us).
+// K-slices of a sum over samples (64x64 tiles, both operands through the transposing loads), at least 256
+// samples per slice.  That kernel keeps 3 work-groups on a CU, 768 on the chip; work-groups beyond a multiple
+// of 768 run a further round on nearly empty CUs, so the slice count decides the time far more than the work
+// does (784-300, 60000 samples, 65 tiles: 16 slices = 1040 work-groups 358 us, 15 slices 316 us, 23 slices =
+// 1495 work-groups 303 us).  The count is the minimum of a model fitted to such sweeps: a K-tile step costs
+// 0.925 us when 3 work-groups share a CU, 0.64 us with 2 and 0.335 us with 1 (last, partial round); every
+// work-group adds 0.006 us for writing and folding its partial tile.
 int pick_splits(int tiles, int K) {
-    int s = std::max(1, kTargetWGs / std::max(1, tiles));
-    s = std::min(s, std::max(1, K / 256));
-    s = std::min(s, 64);
-    if (s >= 6) s = std::max(8, (s + 4) / 8 * 8);
-    return s;
+    constexpr int kSlots = 3 * 256;
+    constexpr double kStep[4] = {0.0, 0.335, 0.64, 0.925};
+    const int smax = std::min(64, std::max(1, K / 256));
+    int best = 1;
+    double best_t = 0.0, one_t = 0.0;
+    for (int s = 1; s <= smax; ++s) {
+        const long long wgs = (long long)tiles * s;
+        const int steps = cdiv(cdiv(K, s), 16);
+        const int rounds = (int)(wgs / kSlots), rest = (int)(wgs % kSlots);
+        const double t = steps * (rounds * kStep[3] + kStep[std::min(3, cdiv(rest, 256))]) + 0.006 * (double)wgs;
+        if (s == 1) one_t = t;
+        if (s == 1 || t < best_t) { best = s; best_t = t; }
+    }
+    // the model is good to a few percent: no slicing unless it promises more than that
+    return one_t <= 1.03 * best_t ? 1 : best;
 }
 
 // Plan of the sums over samples  W_m = T^m^T [Z^{m-1}, 1]  for K samples.  grouped: all layers in
