@@ -111,7 +111,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="BASELINE configuration 1..5 (default 2)")
-    ap.add_argument("--mv-reps", type=int, default=10)
+    ap.add_argument("--mv-reps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain copy kernel of known size (dense copy of stored block P^1) so that "
