@@ -62,7 +62,6 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 struct TnPlan {
-    int tile;                       // 64 or 128
     int splits;
     int k_per_split;
     long long floats[DN_MAX_LAYERS + 1];  // per layer, floats of partial storage

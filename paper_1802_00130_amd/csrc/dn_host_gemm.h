@@ -67,31 +67,17 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Tile variants (measured on MI355X):
-//   128x128, K-tile 16, 2 tiles in flight             large products of K-contiguous operands (>= 1024 tiles)
-//   64x64,   K-tile 16, 4 in flight, pinned schedule  launches of <= 4 work-groups per CU, and sums over samples
-//   64x64,   K-tile 16, 4 in flight                   everything else
+// 64x64 tiles, K-tile 16, 4 K-tiles in flight.  The hand-placed schedule is used for launches of at most 4
+// work-groups per CU and, at every size, when both operands go through the transposing loads (sums over
+// samples); elsewhere the compiler's schedule of the plain loop is as good.
+// 128x128 tiles (one work-group per CU) were dropped: with the tile walk below, 64x64 tiles are as fast or
+// faster at every shape of the path (2048-2000-2000-2000-100: Jacobian sweeps 82.1 -> 71.5 ms, gradient
+// 69.0 -> 61.3 ms; 4096 x 5 - 1000: sweeps 1779 -> 1671 ms, gradient 714 -> 670 ms).
 template <int LA, int LB, int CLS>
-hipError_t launch_gemm(GemmGroup& g, int tile, int splits, hipStream_t st) {
-    if (tile == 128) {
-        finalize_group(g, 128, 128, 16, splits);
-        return launch_gemm_t<128, 128, 16, 2, LA, LB, CLS>(g, st);
-    }
+hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
     finalize_group(g, 64, 64, 16, splits);
-    // the hand-placed schedule wins for small launches, and at every size when both operands go through
-    // the transposing loads (sums over samples)
     if (g.total_tiles <= 4 * 256 || (LA == RT && LB == RT)) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
     return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS>(g, st);
-}
-
-// Measured on MI355X: 64x64 tiles win on every shape of the path except products with both operands
-// K-contiguous and both output dimensions >= 1024, where 128x128 tiles are ~5% faster once there are
-// >= 4 of them per CU.
-int pick_tile(const GemmGroup& g, bool both_k_contiguous) {
-    if (!both_k_contiguous || group_tiles(g, 128, 128) < 1024) return 64;
-    for (int i = 0; i < g.nprob; ++i)
-        if (g.p[i].M < 1024 || g.p[i].N < 1024) return 64;
-    return 128;
 }
 
 // K-slices of a sum over samples (64x64 tiles, both operands through the transposing loads), at least 256
@@ -129,7 +115,6 @@ TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
         if (!grouped && m != only_layer) continue;
         tiles += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
     }
-    pl.tile = 64;
     pl.splits = pick_splits(tiles, K);
     pl.k_per_split = (int)round_up(cdiv(K, pl.splits), kBKmax);
     long long off = 0;

@@ -17,11 +17,10 @@ int forward_layers(dn_ctx* c, const float* theta, const float* Z0, long long ld0
         g.p[0] = mk_problem(zin, ldin, theta + c->woff[m], c->dims[m - 1], zout, c->ld[m], rows, c->dims[m],
                             c->dims[m - 1]);
         g.p[0].bias = theta + c->boff[m];
-        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_FWD);
         DN_HIP(c, ps.err);
         g.p[0].sigmoid = m < c->L ? 1 : 0;
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_FWD>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_FWD>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
         zin = zout;
         ldin = c->ld[m];
@@ -229,12 +228,11 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
                 g.p[m - 1].ldaux = c->ld[L - 1];
             }
         }
-        const int tile = pick_tile(g, true);
         // Small launches (a few tiles per CU) whose longest sum over t is at least twice any other: cut that
         // layer's sum in two halves, written to Q^m and a second buffer that the fused kernel adds on the way
         // in.  The launch then consists of tiles of similar length (measured at 784-300-300-10, |S| = 3000:
         // 30.2 -> 26.8 us).
-        if (fused && tile == 64 && L < DN_MAX_GROUP && group_tiles(g, 64, 64) <= 3 * c->num_cus) {
+        if (fused && L < DN_MAX_GROUP && group_tiles(g, 64, 64) <= 3 * c->num_cus) {
             int big = 0;                       // among the hidden layers: Q^L is read as it is
             for (int k = 1; k + 1 < L; ++k)
                 if (g.p[k].K > g.p[big].K) big = k;
@@ -255,7 +253,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             }
         }
         ProfScope ps(c, KC_GEMM_Q);
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 2. the two passes over the Jacobian blocks
@@ -296,7 +294,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             }
             ProfScope ps(c, KC_GEMM_IMPLICIT);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
         TeamPlan tp;
@@ -341,7 +339,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
             p.alpha = bd ? 2.0f : 1.0f;
             ProfScope ps(c, KC_GEMM_IMPLICIT);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_IMPLICIT>(g, 64, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_IMPLICIT>(g, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
     }
@@ -360,7 +358,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
@@ -429,7 +427,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             if (g.nprob == 0) return DN_OK;
             ProfScope ps(c, KC_GEMM_Q);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 64, 1, c->stream)));
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 1, c->stream)));
             DN_HIP(c, ps.end());
             g.nprob = 0;
             return DN_OK;
@@ -508,7 +506,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             if (g.nprob == 0) return DN_OK;
             ProfScope ps(c, KC_GEMM_TN_MATVEC);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
             DN_HIP(c, ps.end());
             g.nprob = 0;
             return DN_OK;

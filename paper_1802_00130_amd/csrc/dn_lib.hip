@@ -163,7 +163,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
                 p.accumulate = r0 > 0 ? 1 : 0;
                 ProfScope ps(c, KC_GEMM_TN_GRAD);
                 DN_HIP(c, ps.err);
-                DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_GRAD>(g1, plans[m].tile, plans[m].splits, c->stream)));
+                DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_GRAD>(g1, plans[m].splits, c->stream)));
                 DN_HIP(c, ps.end());
             }
             if (m > 1) {
@@ -176,10 +176,9 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
                 p.aux = zprev;
                 p.ldaux = ldprev;
                 p.auxdiv = 1;
-                const int tile = pick_tile(g2, true);
                 ProfScope ps(c, KC_GEMM_BACK);
                 DN_HIP(c, ps.err);
-                DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_BACK>(g2, tile, 1, c->stream)));
+                DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_BACK>(g2, 1, c->stream)));
                 DN_HIP(c, ps.end());
                 cur ^= 1;
             }
@@ -232,10 +231,9 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         p.aux = c->fptr(c->o_ZS[m - 1]);
         p.ldaux = c->ld[m - 1];
         p.auxdiv = nL;
-        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_PREP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_PREP>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_PREP>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     c->s_cur = s;
@@ -486,10 +484,9 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
             g.p[0].aux = c->fptr(c->o_ZS[1]);
             g.p[0].ldaux = c->ld[1];
         }
-        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_Q);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_Q>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 2. forward sweep of the derivative: zdot^m = sigma'(s^m) * (Q^m + zdot^{m-1} W^m), in place in Q^m;
@@ -506,10 +503,9 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
             p.aux = c->fptr(c->o_ZS[m]);
             p.ldaux = c->ld[m];
         }
-        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_ROP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 3. back-propagation with seed J^i v (the factor 2 of B = 2I goes into the final scale):
@@ -523,10 +519,9 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
                        c->dims[m - 1], c->dims[m]);
         p.aux = c->fptr(c->o_ZS[m - 1]);
         p.ldaux = c->ld[m - 1];
-        const int tile = pick_tile(g, true);
         ProfScope ps(c, KC_GEMM_ROP);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, tile, 1, c->stream)));
+        DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_ROP>(g, 1, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. sums over samples for every layer, then out = v/C + (2/|S|) * sums
@@ -544,7 +539,7 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.tile, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     return tn_reduce(c, &pl, false, v, out, 2.0 / (double)s);
