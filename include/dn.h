@@ -189,6 +189,12 @@ typedef struct dn_newton_params {
     int max_trials;     /* >= 1 */
     int cg_min;         /* with independent systems and r_percent > 0: early termination as in dn_cg_sync */
     double r_percent;   /* <= 0: every block runs to its own test */
+    int reuse_forward;  /* nonzero: the caller states that theta, X and Y are exactly as the previous
+                           dn_newton_step on this context left them (same pointers, contents untouched, no
+                           other call on the context in between).  The activations of the accepted line-search
+                           point are then still in the workspace and the gradient skips its forward pass.
+                           Ignored (full evaluation) when the library cannot confirm the pointers and l, after a
+                           step that accepted no point, or when l exceeds l_max. */
 } dn_newton_params;
 
 typedef struct dn_newton_stats {

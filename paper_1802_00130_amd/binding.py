@@ -27,7 +27,8 @@ class NewtonParams(ctypes.Structure):
     _fields_ = [("lam", ctypes.c_double), ("sigma", ctypes.c_double), ("eta", ctypes.c_double),
                 ("eps", ctypes.c_double), ("drop", ctypes.c_double), ("boost", ctypes.c_double),
                 ("cg_max", ctypes.c_int), ("mode", ctypes.c_int), ("combine", ctypes.c_int),
-                ("max_trials", ctypes.c_int), ("cg_min", ctypes.c_int), ("r_percent", ctypes.c_double)]
+                ("max_trials", ctypes.c_int), ("cg_min", ctypes.c_int), ("r_percent", ctypes.c_double),
+                ("reuse_forward", ctypes.c_int)]
 
 
 class NewtonStats(ctypes.Structure):
@@ -289,14 +290,17 @@ def dn_cg_sync(ctx: Context, g: torch.Tensor, lam: float, sigma: float, max_iter
 def dn_newton_step(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor, S: torch.Tensor,
                    d_prev: torch.Tensor, lam: float, cg_max: int, sigma: float = 1e-3, eta: float = 1e-4,
                    eps: float = 1e-5, drop: float = 2.0 / 3.0, boost: float = 1.5, mode: int = DN_FULL,
-                   combine: bool = True, max_trials: int = 30, cg_min: int = 0, r_percent: float = 0.0) -> dict:
+                   combine: bool = True, max_trials: int = 30, cg_min: int = 0, r_percent: float = 0.0,
+                   reuse_forward: bool = False) -> dict:
     """One outer Newton iteration (Section 4.5): theta and d_prev are updated in place; returns the
-    statistics of the step and the next lambda under key "lam"."""
+    statistics of the step and the next lambda under key "lam".  reuse_forward: theta, X and Y are exactly as
+    the previous dn_newton_step on this context left them (the gradient then skips its forward pass)."""
     if not (S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()):
         raise TypeError("S: need a contiguous int32 device tensor")
     l = X.shape[0]
     prm = NewtonParams(float(lam), float(sigma), float(eta), float(eps), float(drop), float(boost), int(cg_max),
-                       int(mode), int(bool(combine)), int(max_trials), int(cg_min), float(r_percent))
+                       int(mode), int(bool(combine)), int(max_trials), int(cg_min), float(r_percent),
+                       int(bool(reuse_forward)))
     st = NewtonStats()
     rc = ctx._lib.dn_newton_step(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
                                  _dev_f32(Y, "Y", l * ctx.dims[-1]), l, S.data_ptr(), S.numel(),

@@ -137,6 +137,13 @@ struct dn_ctx {
     std::vector<Pending> pending;
     std::vector<hipEvent_t> free_events;
 
+    // activations of all l rows left in the workspace by the last accepted line-search point of dn_newton_step
+    bool fwd_valid = false;
+    const float* fwd_theta = nullptr;
+    const float* fwd_X = nullptr;
+    const float* fwd_Y = nullptr;
+    int fwd_l = 0;
+
     float* fptr(size_t off) const { return reinterpret_cast<float*>(ws + off); }
     double* dptr(size_t off) const { return reinterpret_cast<double*>(ws + off); }
 };

@@ -79,6 +79,7 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     c->bound = true;
     c->prepped = false;
     c->team_clean = false;
+    c->fwd_valid = false;
     c->team_used = false;
     c->split_set = false;
     // size of the chip, for kernels whose grid must be resident all at once (default kept if no device answers)
@@ -94,6 +95,7 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
 int dn_forward(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, double* f_host, float* ZL) {
     if (!c || !theta || !X || !Y || !f_host || l < 1) return DN_EINVAL;
     if (!c->bound) return DN_ESTATE;
+    c->fwd_valid = false;
     const int L = c->L, n0 = c->dims[0], nL = c->dims[L];
     // the samples go through in chunks of at most l_max rows that reuse the same activation buffers
     for (int r0 = 0; r0 < l; r0 += c->l_max) {
@@ -107,9 +109,14 @@ int dn_forward(dn_ctx* c, const float* theta, const float* X, const float* Y, in
     return DN_OK;
 }
 
-int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, float* g, double* f_host) {
-    if (!c || !theta || !X || !Y || !g || l < 1) return DN_EINVAL;
-    if (!c->bound) return DN_ESTATE;
+}  // extern "C"
+
+namespace {
+
+// Gradient (Section 2.2).  have_forward: the activations of these l <= l_max rows at this theta are already in
+// the workspace (left there by the line search of the previous Newton step).
+int grad_impl(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, float* g, double* f_host,
+              bool have_forward) {
     const int L = c->L, n0 = c->dims[0], nL = c->dims[L];
     if (L >= 2) {
         int rc = transpose_weights(c, theta, 2, L);
@@ -140,7 +147,7 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
     for (int r0 = 0; r0 < l; r0 += c->l_max) {
         const int rows = std::min(c->l_max, l - r0);
         const float* Xc = X + (long long)r0 * n0;
-        int rc = forward_layers(c, theta, Xc, n0, rows, c->o_Zall, L);
+        int rc = have_forward ? DN_OK : forward_layers(c, theta, Xc, n0, rows, c->o_Zall, L);
         if (rc != DN_OK) return rc;
         // seed 2 (z^L - y) into D[0]
         int cur = 0;
@@ -185,6 +192,17 @@ int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l
         }
     }
     return tn_reduce(c, plans, true, theta, g, 1.0 / (double)l);
+}
+
+}  // namespace
+
+extern "C" {
+
+int dn_grad(dn_ctx* c, const float* theta, const float* X, const float* Y, int l, float* g, double* f_host) {
+    if (!c || !theta || !X || !Y || !g || l < 1) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    c->fwd_valid = false;
+    return grad_impl(c, theta, X, Y, l, g, f_host, false);
 }
 
 int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const int* S, int s) {
@@ -351,7 +369,10 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
 
     // 1-3: gradient on all rows, Jacobian blocks on S, CG direction
     double f0 = 0.0;
-    int rc = dn_grad(c, theta, X, Y, l, g, &f0);
+    const bool have_forward = prm->reuse_forward && c->fwd_valid && c->fwd_theta == theta && c->fwd_X == X &&
+                              c->fwd_Y == Y && c->fwd_l == l && l <= c->l_max;
+    c->fwd_valid = false;
+    int rc = grad_impl(c, theta, X, Y, l, g, &f0, have_forward);
     if (rc != DN_OK) return rc;
     rc = dn_jacobian_prep(c, theta, X, l, S, s);
     if (rc != DN_OK) return rc;
@@ -435,6 +456,11 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
         if (st->rho > 0.75) prm->lambda *= prm->drop;
         else if (!(st->rho >= 0.25)) prm->lambda *= prm->boost;
         DN_HIP(c, hipMemcpyAsync(theta, trial, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c->stream));
+        // the last objective evaluation was the accepted point: its activations are those of the new theta
+        if (l <= c->l_max) {
+            c->fwd_valid = true;
+            c->fwd_theta = theta; c->fwd_X = X; c->fwd_Y = Y; c->fwd_l = l;
+        }
     } else {
         st->alpha = 0.0;
         st->rho = 0.0;

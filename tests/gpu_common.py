@@ -14,7 +14,7 @@ def rel_l2(a, b):
 
 
 class Workload:
-    def __init__(self, cfg, bias_scale=0.0, rows=None):
+    def __init__(self, cfg, bias_scale=0.0, rows=None, l_max=None):
         self.cfg = cfg
         self.X = dn_inputs.make_X(cfg, rows)
         self.Y = dn_inputs.make_Y(cfg, rows)
@@ -27,7 +27,7 @@ class Workload:
         self.dY = torch.from_numpy(self.Y).to(dev)
         self.dtheta = torch.from_numpy(self.theta).to(dev)
         self.dS = torch.from_numpy(self.S).to(dev)
-        self.ctx = dn.Context(cfg.dims, cfg.C, self.l, self.s)
+        self.ctx = dn.Context(cfg.dims, cfg.C, l_max or self.l, self.s)
         self.n = self.ctx.n
 
     def dev(self, a):

@@ -169,3 +169,34 @@ def test_cg_joint_early_termination_matches_the_oracle():
     it_100, _ = dn.dn_cg_sync(w.ctx, w.dev(g32), lam, sigma, 200, 0, 100.0, d)
     assert it_plain == it_100
     w.ctx.close()
+
+
+@pytest.mark.parametrize("chunked", [False, True])
+def test_newton_reuse_forward_changes_nothing(chunked):
+    """Four iterations with the forward pass of the gradient taken from the previous step's accepted line-search
+    point give bit-identical iterates and statistics to four full evaluations.  With l above l_max the
+    request is ignored (the activations of all rows are not in the workspace), with the same outcome."""
+    cfg = dn_inputs.custom((40, 24, 16, 5), l=600, s=200, C=12.0, seed=61)
+    results = []
+    for reuse in (False, True):
+        w = Workload(cfg, bias_scale=0.2, l_max=256 if chunked else None)
+        theta = w.dtheta.clone()
+        d_prev = torch.zeros_like(theta)
+        lam = 1.0
+        stats = []
+        for k in range(4):
+            S = torch.from_numpy(_subset(cfg, k)).to("cuda:0")
+            out = dn.dn_newton_step(w.ctx, theta, w.dX, w.dY, S, d_prev, lam, 6, sigma=0.0, mode=dn.DN_FULL,
+                                    reuse_forward=reuse and k > 0)
+            lam = out["lam"]
+            stats.append(out)
+            if k == 1:
+                # an unrelated call in between must not be mistaken for an untouched workspace
+                dn.dn_forward(w.ctx, w.dtheta, w.dX, w.dY)
+        results.append((theta.clone(), d_prev.clone(), stats))
+        w.ctx.close()
+    (th_a, d_a, st_a), (th_b, d_b, st_b) = results
+    assert torch.equal(th_a, th_b) and torch.equal(d_a, d_b)
+    for a, b in zip(st_a, st_b):
+        assert a == b
+    assert all(s["alpha"] > 0 for s in st_a)
