@@ -70,7 +70,8 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
                                c->n, 1.0f);
             DN_HIP(c, hipGetLastError());
         } else {
-            rc = gn_matvec(c, p, q, mode);
+            // the fold at the end of the product also leaves the partial sums of p^T (G + lambda I) p
+            rc = gn_matvec(c, p, q, mode, part1, (float)lambda);
             if (rc != DN_OK) return rc;
         }
         const CgState* cur = st + (iters & 1);
@@ -78,8 +79,10 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
         {
             ProfScope ps(c, KC_CG_VEC);
             DN_HIP(c, ps.err);
-            hipLaunchKernelGGL(cg_dot_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda, part1);
-            DN_HIP(c, hipGetLastError());
+            if (part) {
+                hipLaunchKernelGGL(cg_dot_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda, part1);
+                DN_HIP(c, hipGetLastError());
+            }
             hipLaunchKernelGGL(cg_update_dr_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, part1, p, q,
                                (float)lambda, d_cg, r, part2);
             DN_HIP(c, hipGetLastError());

@@ -60,14 +60,29 @@ int objective(dn_ctx* c, const float* theta, const float* Y, int rows, int l, bo
     return DN_OK;
 }
 
-// out = x/C + scale * (folded partial sums), theta layout
+// Work-groups of tn_reduce_kernel: layer m's items (row, 1024 columns) are shared by blk[m+1] - blk[m]
+// work-groups, about 1000 in all (at most DN_MAX_PARTIALS: each may emit one partial sum).
+int reduce_grid(const dn_ctx* c, int* blk /* L + 2 entries, index 1..L+1 */) {
+    long long total = 0;
+    for (int m = 1; m <= c->L; ++m) total += (long long)c->dims[m] * cdiv(c->dims[m - 1] + 1, 1024);
+    int blocks = 0;
+    for (int m = 1; m <= c->L; ++m) {
+        const long long items = (long long)c->dims[m] * cdiv(c->dims[m - 1] + 1, 1024);
+        blk[m] = blocks;
+        blocks += (int)std::max<long long>(1, std::min<long long>(items, items * 1000 / total));
+    }
+    blk[c->L + 1] = blocks;
+    return blocks;
+}
+
+// out = x/C + scale * (folded partial sums), theta layout.  dot (nullable): see tn_reduce_kernel.
 int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan for all */, bool per_layer,
-              const float* x, float* out, double scale) {
+              const float* x, float* out, double scale, double* dot = nullptr, float lambda = 0.f) {
     ReduceArgs ra;
     std::memset(&ra, 0, sizeof(ra));
     ra.L = c->L;
     for (int m = 0; m <= c->L; ++m) ra.n[m] = c->dims[m];
-    int blocks = 0;
+    const int blocks = reduce_grid(c, ra.blk_begin);
     for (int m = 1; m <= c->L; ++m) {
         const TnPlan& pl = per_layer ? plans[m] : plans[0];
         ra.off[m] = c->woff[m];
@@ -76,14 +91,12 @@ int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan fo
         ra.split_stride[m] = (long long)c->dims[m] * c->ldw[m];
         ra.splits[m] = pl.splits;
         ra.chunks[m] = cdiv(c->dims[m - 1] + 1, 1024);
-        ra.blk_begin[m] = blocks;
-        blocks += c->dims[m] * ra.chunks[m];
+        ra.items[m] = c->dims[m] * ra.chunks[m];
     }
-    ra.blk_begin[c->L + 1] = blocks;
     ProfScope ps(c, KC_TN_REDUCE);
     DN_HIP(c, ps.err);
     hipLaunchKernelGGL(tn_reduce_kernel, dim3(blocks), dim3(256), 0, c->stream, ra, x, out, (float)(1.0 / c->C),
-                       (float)scale);
+                       (float)scale, dot, lambda);
     DN_HIP(c, hipGetLastError());
     DN_HIP(c, ps.end());
     return DN_OK;
@@ -206,7 +219,8 @@ int team_status(dn_ctx* c) {
 int gn_matvec_part(dn_ctx* c, const float* v, float* out);
 
 // out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
-int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
+// dot, lambda: passed on to the fold of the sums over samples (not in partition mode)
+int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nullptr, float lambda = 0.f) {
     if (mode == DN_PARTITION) return c->split_set ? gn_matvec_part(c, v, out) : DN_ESTATE;
     const int L = c->L, s = c->s_cur, nL = c->dims[L];
     StreamArgs a;
@@ -362,7 +376,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode) {
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
-    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s);
+    return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s, dot, lambda);
 }
 
 void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
@@ -395,6 +409,20 @@ void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
         b += (int)((sg.off[k + 1] - sg.off[k] + chunk - 1) / chunk);
     }
     sg.cb[sg.nseg] = b;
+    // where the partial sums of p^T A p come from: the fold of the product (full and per-layer systems: its
+    // work-groups are grouped by layer), or cg_dot_kernel on this grid (partitions)
+    if (mode == DN_PARTITION) {
+        for (int k = 0; k <= sg.nseg; ++k) sg.pb[k] = sg.cb[k];
+    } else {
+        int blk[DN_MAX_LAYERS + 2];
+        const int blocks = reduce_grid(c, blk);
+        if (mode == DN_BLOCKDIAG) {
+            for (int m = 1; m <= c->L + 1; ++m) sg.pb[m - 1] = blk[m];
+        } else {
+            sg.pb[0] = 0;
+            sg.pb[1] = blocks;
+        }
+    }
 }
 
 bool bad_mode(int mode) { return mode != DN_FULL && mode != DN_BLOCKDIAG && mode != DN_PARTITION; }

@@ -18,62 +18,84 @@ struct ReduceArgs {
     long long ldw[DN_MAX_LAYERS + 1];
     long long split_stride[DN_MAX_LAYERS + 1];
     int splits[DN_MAX_LAYERS + 1];
-    int blk_begin[DN_MAX_LAYERS + 2];   // first work-group of layer m; one work-group = (row j, 1024 columns)
+    int blk_begin[DN_MAX_LAYERS + 2];   // first work-group of layer m; its work-groups share the layer's items
+    int items[DN_MAX_LAYERS + 1];       // items of layer m; one item = (row j, 1024 columns)
     int chunks[DN_MAX_LAYERS + 1];      // 1024-column chunks per row of layer m
 };
 
 typedef float f32x4v __attribute__((ext_vector_type(4), aligned(4)));
 
+// dot (nullable): partial sums of x^T (out + lambda x) per work-group, in fp64; the work-groups of layer m are
+// [blk_begin[m], blk_begin[m+1]), so a conjugate gradient step whose product ends here gets p^T (G + lambda I) p
+// (whole, or per layer) without another pass over the two vectors.
 __global__ __launch_bounds__(256) void tn_reduce_kernel(const ReduceArgs a, const float* __restrict__ x,
-                                                        float* __restrict__ out, float invC, float scale) {
+                                                        float* __restrict__ out, float invC, float scale,
+                                                        double* __restrict__ dot, float lambda) {
+    __shared__ double red[4];
     int m = 1;
 #pragma unroll
     for (int k = 2; k <= DN_MAX_LAYERS; ++k)
         if (k <= a.L && (int)blockIdx.x >= a.blk_begin[k]) m = k;
-    const int loc = (int)blockIdx.x - a.blk_begin[m];
-    const int j = loc / a.chunks[m];
-    const int t = (loc - j * a.chunks[m]) * 1024 + 4 * (int)threadIdx.x;
+    const int nb = a.blk_begin[m + 1] - a.blk_begin[m];
     const int np = a.n[m - 1];
-    if (t > np) return;                       // columns 0..np (np = bias column)
-    const float* __restrict__ w = a.W[m] + (long long)j * a.ldw[m] + t;   // 16-byte aligned: ldw % 4 == 0
     const long long ss = a.split_stride[m];
     const int ns = a.splits[m];
-    // fixed summation order: slices in increasing order, four partial chains
-    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0, acc2 = acc0, acc3 = acc0;
-    int sidx = 0;
-    for (; sidx + 4 <= ns; sidx += 4) {
-        const float4 w0 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 0) * ss);
-        const float4 w1 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 1) * ss);
-        const float4 w2 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 2) * ss);
-        const float4 w3 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 3) * ss);
-        acc0.x += w0.x; acc0.y += w0.y; acc0.z += w0.z; acc0.w += w0.w;
-        acc1.x += w1.x; acc1.y += w1.y; acc1.z += w1.z; acc1.w += w1.w;
-        acc2.x += w2.x; acc2.y += w2.y; acc2.z += w2.z; acc2.w += w2.w;
-        acc3.x += w3.x; acc3.y += w3.y; acc3.z += w3.z; acc3.w += w3.w;
-    }
-    for (; sidx < ns; ++sidx) {
-        const float4 w0 = *reinterpret_cast<const float4*>(w + (long long)sidx * ss);
-        acc0.x += w0.x; acc0.y += w0.y; acc0.z += w0.z; acc0.w += w0.w;
-    }
-    float s4[4] = {(acc0.x + acc1.x) + (acc2.x + acc3.x), (acc0.y + acc1.y) + (acc2.y + acc3.y),
-                   (acc0.z + acc1.z) + (acc2.z + acc3.z), (acc0.w + acc1.w) + (acc2.w + acc3.w)};
-    const long long wbase = a.off[m] + (long long)j * np;                // weight (j, t) sits at wbase + t
-    const long long bidx = a.off[m] + (long long)np * a.n[m] + j;        // bias j
-    if (t + 3 < np) {
-        const f32x4v xv = *reinterpret_cast<const f32x4v*>(x + wbase + t);
-        f32x4v o;
-        o[0] = xv[0] * invC + scale * s4[0];
-        o[1] = xv[1] * invC + scale * s4[1];
-        o[2] = xv[2] * invC + scale * s4[2];
-        o[3] = xv[3] * invC + scale * s4[3];
-        *reinterpret_cast<f32x4v*>(out + wbase + t) = o;
-    } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int tt = t + c;
-            if (tt < np)       out[wbase + tt] = x[wbase + tt] * invC + scale * s4[c];
-            else if (tt == np) out[bidx] = x[bidx] * invC + scale * s4[c];
+    double dacc = 0.0;
+    for (int item = (int)blockIdx.x - a.blk_begin[m]; item < a.items[m]; item += nb) {
+        const int j = item / a.chunks[m];
+        const int t = (item - j * a.chunks[m]) * 1024 + 4 * (int)threadIdx.x;
+        if (t > np) continue;                     // columns 0..np (np = bias column)
+        const float* __restrict__ w = a.W[m] + (long long)j * a.ldw[m] + t;   // 16-byte aligned: ldw % 4 == 0
+        // fixed summation order: slices in increasing order, four partial chains
+        float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0, acc2 = acc0, acc3 = acc0;
+        int sidx = 0;
+        for (; sidx + 4 <= ns; sidx += 4) {
+            const float4 w0 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 0) * ss);
+            const float4 w1 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 1) * ss);
+            const float4 w2 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 2) * ss);
+            const float4 w3 = *reinterpret_cast<const float4*>(w + (long long)(sidx + 3) * ss);
+            acc0.x += w0.x; acc0.y += w0.y; acc0.z += w0.z; acc0.w += w0.w;
+            acc1.x += w1.x; acc1.y += w1.y; acc1.z += w1.z; acc1.w += w1.w;
+            acc2.x += w2.x; acc2.y += w2.y; acc2.z += w2.z; acc2.w += w2.w;
+            acc3.x += w3.x; acc3.y += w3.y; acc3.z += w3.z; acc3.w += w3.w;
         }
+        for (; sidx < ns; ++sidx) {
+            const float4 w0 = *reinterpret_cast<const float4*>(w + (long long)sidx * ss);
+            acc0.x += w0.x; acc0.y += w0.y; acc0.z += w0.z; acc0.w += w0.w;
+        }
+        float s4[4] = {(acc0.x + acc1.x) + (acc2.x + acc3.x), (acc0.y + acc1.y) + (acc2.y + acc3.y),
+                       (acc0.z + acc1.z) + (acc2.z + acc3.z), (acc0.w + acc1.w) + (acc2.w + acc3.w)};
+        const long long wbase = a.off[m] + (long long)j * np;                // weight (j, t) sits at wbase + t
+        const long long bidx = a.off[m] + (long long)np * a.n[m] + j;        // bias j
+        if (t + 3 < np) {
+            const f32x4v xv = *reinterpret_cast<const f32x4v*>(x + wbase + t);
+            f32x4v o;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = xv[c] * invC + scale * s4[c];
+            *reinterpret_cast<f32x4v*>(out + wbase + t) = o;
+            if (dot) {
+                double d4[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) d4[c] = (double)xv[c] * (double)(o[c] + lambda * xv[c]);
+                dacc += (d4[0] + d4[1]) + (d4[2] + d4[3]);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int tt = t + c;
+                if (tt <= np) {
+                    const long long e = tt < np ? wbase + tt : bidx;
+                    const float xe = x[e];
+                    const float o = xe * invC + scale * s4[c];
+                    out[e] = o;
+                    if (dot) dacc += (double)xe * (double)(o + lambda * xe);
+                }
+            }
+        }
+    }
+    if (dot) {
+        dacc = block_sum_d(dacc, red);
+        if (threadIdx.x == 0) dot[blockIdx.x] = dacc;
     }
 }
 
@@ -86,6 +108,7 @@ struct CgSegs {
     int chunk;                           // elements per work-group
     long long off[DN_MAX_SEGS + 1];      // segment k covers [off[k], off[k+1])
     int cb[DN_MAX_SEGS + 1];             // first work-group of segment k; cb[nseg] = grid size
+    int pb[DN_MAX_SEGS + 1];             // partial sums of p^T A p that belong to segment k: [pb[k], pb[k+1])
 };
 
 struct CgState {                         // lives in device memory, one per iteration parity
@@ -189,7 +212,7 @@ __global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, cons
         if (threadIdx.x == 0) rr_partials[blockIdx.x] = 0.0;
         return;
     }
-    const double pq = block_sum_range(pq_partials, sg.cb[seg], sg.cb[seg + 1], red);
+    const double pq = block_sum_range(pq_partials, sg.pb[seg], sg.pb[seg + 1], red);
     const float alpha = (float)(st->rho[seg] / pq);
     double acc = 0.0;
     cg_sweep(lo, hi,
