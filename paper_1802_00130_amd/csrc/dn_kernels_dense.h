@@ -10,12 +10,17 @@ namespace dn {
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ X, const int* __restrict__ S,
                                                           float* __restrict__ XS, int s, int n0, int l,
                                                           long long ldx, long long ldxs) {
-    const long long total = (long long)s * n0;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
-        const int i = (int)(e / n0);
-        const int t = (int)(e - (long long)i * n0);
+    // one wave per row at a time: 4 rows per work-group and pass
+    const int lane = threadIdx.x & 63;
+    for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < s; i += gridDim.x * 4) {
         const int row = min(max(S[i], 0), l - 1);  // ids outside [0, l) are clamped, never dereferenced
-        XS[(long long)i * ldxs + t] = X[(long long)row * ldx + t];
+        const float* __restrict__ src = X + (long long)row * ldx;
+        float* __restrict__ dst = XS + (long long)i * ldxs;
+        // 16-byte accesses that only assume the alignment of a float (rows of X start anywhere)
+        typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+        const int n4 = n0 & ~3;
+        for (int t = 4 * lane; t < n4; t += 256) *reinterpret_cast<f4u*>(dst + t) = *reinterpret_cast<const f4u*>(src + t);
+        if (n4 + lane < n0) dst[n4 + lane] = src[n4 + lane];
     }
 }
 

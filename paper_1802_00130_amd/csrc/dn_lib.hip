@@ -213,7 +213,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
     {
         ProfScope ps(c, KC_GATHER);
         DN_HIP(c, ps.err);
-        hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for((long long)s * c->dims[0])), dim3(256), 0, c->stream, X,
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(std::min(cdiv(s, 4), 256 * 16)), dim3(256), 0, c->stream, X,
                            S, c->fptr(c->o_ZS[0]), s, c->dims[0], l, (long long)c->dims[0], c->ld[0]);
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
