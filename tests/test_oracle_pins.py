@@ -575,3 +575,49 @@ def test_input_generator_shapes_and_ranges():
     thd = dn_inputs.make_theta(cd, init="dense")
     sds = [thd[w:w + cd.dims[m] * cd.dims[m + 1]].std() for m, (w, _) in enumerate(dn_inputs.layer_offsets(cd.dims))]
     np.testing.assert_allclose(sds, [0.1, 0.05, 0.001], rtol=0.02)
+
+
+def _golden_split_structures():
+    import os
+    rows, weights = [], []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "split_structures.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [p.strip() for p in line.split(";")]
+            if parts[0] == "weights":
+                weights.append((parts[1], int(parts[2]), int(parts[3])))
+            else:
+                rows.append((parts[0], tuple(int(x) for x in parts[1].split("-")),
+                             tuple(int(x) for x in parts[2].split("-")), int(parts[3])))
+    return rows, weights
+
+
+def test_partition_counts_match_the_papers_table():
+    """Every (network, split structure) pair the paper prints gives the printed number of partitions, the
+    partitions tile the variables exactly once, each holds |T_{m-1}| x |T_m| weights (plus the biases of its
+    output group when it belongs to the first input group), and the Pendigits weight counts come out as printed."""
+    rows, weights = _golden_split_structures()
+    assert len(rows) == 10
+    by_name = {}
+    for name, dims, split, count in rows:
+        sets = orc.partition_index_sets(dims, split)
+        assert len(sets) == count, name
+        n = orc.num_params(dims)
+        seen = np.zeros(n, dtype=np.int8)
+        for idx in sets:
+            seen[idx] += 1
+        assert np.all(seen == 1), name
+        w_counts, k = [], 0
+        for m in range(1, len(dims)):
+            ba, bb = orc.group_bounds(dims[m - 1], split[m - 1]), orc.group_bounds(dims[m], split[m])
+            for a in range(split[m - 1]):
+                for b in range(split[m]):
+                    w = (ba[a + 1] - ba[a]) * (bb[b + 1] - bb[b])
+                    assert sets[k].size == w + ((bb[b + 1] - bb[b]) if a == 0 else 0), (name, m, a, b)
+                    w_counts.append(w)
+                    k += 1
+        by_name[name] = w_counts
+    for name, largest, smallest in weights:
+        assert max(by_name[name]) == largest and min(by_name[name]) == smallest
