@@ -43,3 +43,23 @@ class Workload:
     def oracle_matvec(self, v, blockdiag=False):
         f = orc.gn_matvec_blockdiag if blockdiag else orc.gn_matvec
         return f(self.theta.astype(np.float64), self.cfg.dims, self.cfg.C, self.XS64, v.astype(np.float64))
+
+
+def cg_fp32_vectors(oracle, theta, dims, C, XS, g, lam, iters):
+    """The oracle's CG (full system) with every vector rounded to fp32 after each update and the step lengths
+    rounded to fp32, products and inner products in fp64: what limits a CG whose vectors are stored in fp32,
+    whatever computes the products.  Test-side arithmetic on top of the oracle's product."""
+    f32 = lambda a: a.astype(np.float32).astype(np.float64)
+    d = np.zeros_like(g)
+    r = f32(-g)
+    p = r.copy()
+    rho = r @ r
+    for _ in range(iters):
+        q = f32(oracle.gn_matvec(theta, dims, C, XS, p))
+        alpha = np.float64(np.float32(rho / (p @ (q + lam * p))))
+        d = f32(d + alpha * p)
+        r = f32(r - alpha * f32(q + f32(lam * p)))
+        rho_new = r @ r
+        p = f32(r + np.float64(np.float32(rho_new / rho)) * p)
+        rho = rho_new
+    return d
