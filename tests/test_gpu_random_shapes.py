@@ -79,11 +79,13 @@ def test_random_shape(k):
 
 
 @pytest.mark.parametrize("k", [81, 87])
-def test_cg_without_hidden_layer_is_limited_by_fp32_vectors(k):
-    """Two shapes found by running this file's recipe on further seeds: networks without a hidden layer whose
-    gradient is dominated by one direction.  After six CG iterations the fp32 iterate is 1-2e-3 away from the
-    fp64 one, above the 1e-3 bar of the other cases.  The difference is that of storing the CG vectors in fp32:
-    the oracle's own recurrence with its vectors rounded to fp32 (products and inner products still fp64) lands
+def test_cg_without_hidden_layer_follows_the_fp32_recurrence(k):
+    """Two shapes found by running this file's recipe on further seeds: networks without a hidden layer, whose
+    small quadratic systems have all but converged after six CG iterations (residual 3-4e-4 of |g|).  The sixth
+    fp32 iterate is 1-2e-3 away from the fp64 one, above the 1e-3 bar of the other cases, because a nearly
+    converged Krylov iterate is only determined up to about its residual: rounding any one of r, p, G p or the
+    step lengths to fp32 moves it that far.  What can be checked is that the device follows the recurrence: the
+    oracle's CG with its vectors and step lengths rounded to fp32 (products and inner products still fp64) lands
     within 1e-4 of the device's result and equally far from the fp64 iterate."""
     from tests.gpu_common import cg_fp32_vectors
     cfg, _ = _draw(k)
