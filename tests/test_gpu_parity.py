@@ -282,3 +282,50 @@ def test_wide_hidden_layers_small_output(name):
     assert (prof["jv_jtv_fused"][1] == 2) == name.startswith("fused2")
     assert (prof["jv_rows"][1] == 2) == name.startswith("twopass")
     w.ctx.close()
+
+
+def test_two_contexts_on_two_streams():
+    """Two contexts for different networks, each bound to a stream of its own (default priority), with their
+    calls interleaved from the host: every result matches the oracle, so nothing is shared between contexts
+    and all work of a context stays on its stream."""
+    cfg_a = dn_inputs.custom((30, 20, 12, 4), l=300, s=90, C=6.0, seed=71)
+    cfg_b = dn_inputs.custom((18, 40, 35), l=260, s=70, C=2.0, seed=72)       # n_L > 16: team kernel
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    work = []
+    for cfg, st in zip((cfg_a, cfg_b), streams):
+        X, Y = dn_inputs.make_X(cfg), dn_inputs.make_Y(cfg)
+        theta, S, v = dn_inputs.make_theta(cfg, bias_scale=0.3), dn_inputs.make_subset(cfg), dn_inputs.make_probe(cfg, 0)
+        t = lambda a: torch.from_numpy(a).to("cuda:0")
+        ctx = dn.Context(cfg.dims, cfg.C, cfg.l, cfg.s, stream=st)
+        work.append(dict(cfg=cfg, ctx=ctx, st=st, X=X, Y=Y, theta=theta, S=S, v=v, dX=t(X), dY=t(Y), dth=t(theta),
+                         dS=t(S), dv=t(v)))
+    torch.cuda.synchronize()
+    for w in work:
+        for k in ("g", "out_full", "out_bd", "d"):
+            w[k] = torch.empty(w["ctx"].n, dtype=torch.float32, device="cuda:0")
+    # interleave: the same step of both contexts back to back, no synchronisation in between
+    for w in work:
+        dn.dn_grad(w["ctx"], w["dth"], w["dX"], w["dY"], w["g"], want_f=False)
+    for w in work:
+        dn.dn_jacobian_prep(w["ctx"], w["dth"], w["dX"], w["dS"])
+    for _ in range(3):
+        for w in work:
+            dn.dn_gn_matvec(w["ctx"], w["dv"], w["out_full"], dn.DN_FULL)
+            dn.dn_gn_matvec(w["ctx"], w["dv"], w["out_bd"], dn.DN_BLOCKDIAG)
+    for w in work:
+        w["iters"], _ = dn.dn_cg(w["ctx"], w["g"], 1.0, 0.0, 5, dn.DN_FULL, w["d"])
+    for st in streams:
+        st.synchronize()
+    for w in work:
+        cfg = w["cfg"]
+        th64, X64, Y64 = w["theta"].astype(np.float64), w["X"].astype(np.float64), w["Y"].astype(np.float64)
+        XS = X64[w["S"]]
+        g_ref, _ = orc.grad(th64, cfg.dims, cfg.C, X64, Y64)
+        assert rel_l2(w["g"].cpu().numpy(), g_ref) <= TOL
+        v64 = w["v"].astype(np.float64)
+        assert rel_l2(w["out_full"].cpu().numpy(), orc.gn_matvec(th64, cfg.dims, cfg.C, XS, v64)) <= TOL
+        assert rel_l2(w["out_bd"].cpu().numpy(), orc.gn_matvec_blockdiag(th64, cfg.dims, cfg.C, XS, v64)) <= TOL
+        g32 = w["g"].cpu().numpy().astype(np.float64)
+        d_ref, _, _ = orc.cg(th64, cfg.dims, cfg.C, XS, g32, 1.0, 5)
+        assert w["iters"] == 5 and rel_l2(w["d"].cpu().numpy(), d_ref) <= 1e-3
+        w["ctx"].close()
