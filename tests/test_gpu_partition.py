@@ -117,17 +117,10 @@ def test_newton_step_and_joint_termination_over_partitions():
 
 
 def test_partition_counts_of_the_papers_split_structures():
-    """dn_set_split gives the partition counts the paper prints for its own networks (tests/golden), and its
-    partition-major index map, read back through a CG run on a one-hot gradient, is not needed for that: the
-    count alone is checked here, the map by the parity cases above."""
-    import os
-    rows = []
-    with open(os.path.join(os.path.dirname(__file__), "golden", "split_structures.txt")) as fh:
-        for line in fh:
-            parts = [p.strip() for p in line.strip().split(";")]
-            if len(parts) == 4 and parts[0] != "weights" and not parts[0].startswith("#"):
-                rows.append((parts[0], tuple(int(x) for x in parts[1].split("-")),
-                             tuple(int(x) for x in parts[2].split("-")), int(parts[3])))
+    """dn_set_split gives the partition counts the paper prints for its own networks (tests/golden).  Only the
+    count is checked here; the index map behind it is exercised by the parity cases above."""
+    from tests.golden_io import split_structures
+    rows, _ = split_structures()
     assert len(rows) == 10
     for name, dims, split, count in rows:
         print(f"[split] {name} {dims} {split}", flush=True)

@@ -577,28 +577,12 @@ def test_input_generator_shapes_and_ranges():
     np.testing.assert_allclose(sds, [0.1, 0.05, 0.001], rtol=0.02)
 
 
-def _golden_split_structures():
-    import os
-    rows, weights = [], []
-    with open(os.path.join(os.path.dirname(__file__), "golden", "split_structures.txt")) as fh:
-        for line in fh:
-            line = line.strip()
-            if not line or line.startswith("#"):
-                continue
-            parts = [p.strip() for p in line.split(";")]
-            if parts[0] == "weights":
-                weights.append((parts[1], int(parts[2]), int(parts[3])))
-            else:
-                rows.append((parts[0], tuple(int(x) for x in parts[1].split("-")),
-                             tuple(int(x) for x in parts[2].split("-")), int(parts[3])))
-    return rows, weights
-
-
 def test_partition_counts_match_the_papers_table():
     """Every (network, split structure) pair the paper prints gives the printed number of partitions, the
     partitions tile the variables exactly once, each holds |T_{m-1}| x |T_m| weights (plus the biases of its
     output group when it belongs to the first input group), and the Pendigits weight counts come out as printed."""
-    rows, weights = _golden_split_structures()
+    from tests.golden_io import split_structures
+    rows, weights = split_structures()
     assert len(rows) == 10
     by_name = {}
     for name, dims, split, count in rows:
