@@ -67,9 +67,9 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-// 64x64 tiles, K-tile 16, 4 K-tiles in flight (2 for short sums).  The hand-placed schedule is used for launches of at most 4
-// work-groups per CU and, at every size, when both operands go through the transposing loads (sums over
-// samples); elsewhere the compiler's schedule of the plain loop is as good.
+// 64x64 tiles, K-tile 16, 4 K-tiles in flight (2 for short sums).  The hand-placed schedule is used for
+// launches of at most 4 work-groups per CU and, at every size, when both operands go through the transposing
+// loads (sums over samples); elsewhere the compiler's schedule of the plain loop is as good.
 // 128x128 tiles (one work-group per CU) were dropped: with the XCD-aware tile walk, 64x64 tiles are as fast or
 // faster at every shape of the path (2048-2000-2000-2000-100: Jacobian sweeps 82.1 -> 71.5 ms, gradient
 // 69.0 -> 61.3 ms; 4096 x 5 - 1000: sweeps 1779 -> 1671 ms, gradient 714 -> 670 ms).
