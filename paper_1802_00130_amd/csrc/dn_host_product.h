@@ -508,14 +508,14 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         if (L >= 2) {
             ProfScope ps(c, KC_JV);
             DN_HIP(c, ps.err);
-            hipLaunchKernelGGL(jv_part_kernel, dim3(s * cdiv(nL, 4)), dim3(256), 0, c->stream, a);
+            hipLaunchKernelGGL((jv_part_kernel<2>), dim3(s * cdiv(nL, 8)), dim3(256), 0, c->stream, a);
             DN_HIP(c, hipGetLastError());
             DN_HIP(c, ps.end());
         }
         ProfScope ps(c, KC_JTV);
         DN_HIP(c, ps.err);
         int chunks = 1;
-        for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 256);
+        for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 1024);
         int most = 1;
         for (int m = 1; m < L; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
         const size_t lds = sizeof(float) * (size_t)most * nL;

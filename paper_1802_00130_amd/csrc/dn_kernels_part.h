@@ -38,72 +38,90 @@ __device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
     return g;
 }
 
-// work-group = (sample, block of 4 outputs); each wave takes one row u of every hidden layer's block
+// work-group = (sample, block of 8 outputs); each wave takes two rows u of every hidden layer's block
+template <int RW>
 __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
-    constexpr int UB = 4;
+    constexpr int UB = 4 * RW;              // rows per work-group: wave w takes rows u0 + w + 4 k, k < RW, together
     const int ublocks = (a.nL + UB - 1) / UB;
     const int i = blockIdx.x / ublocks;
     const int u0 = (blockIdx.x - i * ublocks) * UB;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long slab = (long long)a.s * a.ldr;
-    for (int uu = wave; uu < UB; uu += 4) {
-        const int u = u0 + uu;
-        if (u >= a.nL) break;
-        for (int m = 1; m < a.L; ++m) {
-            const int ga = a.split[m - 1], gb = a.split[m];
-            const float* __restrict__ prow = a.P[m] + ((long long)i * a.nL + u) * a.ld[m];
-            double acc[DN_MAX_SPLIT][DN_MAX_SPLIT];
+    if (u0 + wave >= a.nL) return;
+    int urow[RW];
 #pragma unroll
-            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+    for (int k = 0; k < RW; ++k) urow[k] = u0 + wave + 4 * k;
+    for (int m = 1; m < a.L; ++m) {
+        const int ga = a.split[m - 1], gb = a.split[m];
+        const float* __restrict__ prow[RW];
 #pragma unroll
-                for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] = 0.0;
-            // four columns at a time (rows are 16-byte aligned and padded to a multiple of 4 floats; the padding of
-            // P and Q holds no data, so the last, partial group of four is masked); a group boundary may fall
-            // inside a group of four, hence the per-column group index
-            const int nm4 = (a.n[m] + 3) >> 2;
-            for (int c4 = lane; c4 < nm4; c4 += 64) {
+        for (int k = 0; k < RW; ++k)      // rows past n_L repeat the first one; their sums are not stored
+            prow[k] = a.P[m] + ((long long)i * a.nL + (urow[k] < a.nL ? urow[k] : urow[0])) * a.ld[m];
+        // one output group at a time: its columns [lo, hi) are contiguous, so the sums of the ga partitions
+        // that share them need no per-column bookkeeping.  Four columns per lane and step (rows are 16-byte
+        // aligned and padded to a multiple of 4 floats); a group boundary may fall inside such a group of
+        // four, which is then read for both neighbours and masked.
+        for (int y = 0; y < gb; ++y) {
+            const int lo = a.bound[m][y], hi = a.bound[m][y + 1];
+            double acc[RW][DN_MAX_SPLIT];
+#pragma unroll
+            for (int k = 0; k < RW; ++k)
+#pragma unroll
+                for (int x = 0; x < DN_MAX_SPLIT; ++x) acc[k][x] = 0.0;
+            for (int c4 = (lo >> 2) + lane; 4 * c4 < hi; c4 += 64) {
                 const int j = 4 * c4;
-                const float4 p4 = *reinterpret_cast<const float4*>(prow + j);
-                const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
-                int bj[4];
+                float4 p4[RW];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) bj[e] = (j + e < a.n[m]) ? group_of(a.bound[m], gb, j + e) : -1;
+                for (int k = 0; k < RW; ++k) p4[k] = *reinterpret_cast<const float4*>(prow[k] + j);
+                if (j < lo || j + 3 >= hi) {
+#pragma unroll
+                    for (int k = 0; k < RW; ++k) {
+                        if (j + 0 < lo || j + 0 >= hi) p4[k].x = 0.f;
+                        if (j + 1 < lo || j + 1 >= hi) p4[k].y = 0.f;
+                        if (j + 2 < lo || j + 2 >= hi) p4[k].z = 0.f;
+                        if (j + 3 < lo || j + 3 >= hi) p4[k].w = 0.f;
+                    }
+                }
 #pragma unroll
                 for (int x = 0; x < DN_MAX_SPLIT; ++x) {
                     if (x < ga) {
-                        const float4 q4 = *reinterpret_cast<const float4*>(a.Qp[m] + ((long long)x * a.s + i) * a.ld[m] + j);
-                        const float qe[4] = {q4.x, q4.y, q4.z, q4.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const double t = bj[e] >= 0 ? (double)pe[e] * (double)qe[e] : 0.0;
-#pragma unroll
-                            for (int y = 0; y < DN_MAX_SPLIT; ++y) acc[x][y] += (y == bj[e]) ? t : 0.0;
+                        float4 q4 = *reinterpret_cast<const float4*>(a.Qp[m] + ((long long)x * a.s + i) * a.ld[m] + j);
+                        // the padding of Q holds no data: keep it out of the products (0 * NaN)
+                        if (j + 3 >= a.n[m]) {
+                            if (j + 1 >= a.n[m]) q4.y = 0.f;
+                            if (j + 2 >= a.n[m]) q4.z = 0.f;
+                            q4.w = 0.f;
                         }
+#pragma unroll
+                        for (int k = 0; k < RW; ++k)
+                            acc[k][x] += ((double)p4[k].x * q4.x + (double)p4[k].y * q4.y) +
+                                         ((double)p4[k].z * q4.z + (double)p4[k].w * q4.w);
                     }
                 }
             }
 #pragma unroll
-            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+            for (int x = 0; x < DN_MAX_SPLIT; ++x) {
+                if (x < ga) {
+                    float* r = a.R + (long long)(a.part_base[m] + x * gb + y) * slab + (long long)i * a.ldr;
 #pragma unroll
-                for (int y = 0; y < DN_MAX_SPLIT; ++y) {
-                    if (x < ga && y < gb) {
-                        const double t = wave_sum_d(acc[x][y]);
-                        if (lane == 0)
-                            a.R[(long long)(a.part_base[m] + x * gb + y) * slab + (long long)i * a.ldr + u] = (float)t;
+                    for (int k = 0; k < RW; ++k) {
+                        const double t = wave_sum_d(acc[k][x]);
+                        if (lane == 0 && urow[k] < a.nL) r[urow[k]] = (float)t;
                     }
                 }
+            }
         }
     }
 }
 
-// work-group = (sample, layer, chunk of 256 columns); one thread per column.  Layer L: t^{L,a} = 2 q^{L,a}.
+// work-group = (sample, layer, chunk of 1024 columns); four columns per thread.  Layer L: t^{L,a} = 2 q^{L,a}.
 __global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chunks_total) {
     extern __shared__ float rbar[];          // [ga][gb][nL] of this layer
     const int i = blockIdx.x / chunks_total;
     int c = blockIdx.x - i * chunks_total;
     int m = 1;
     for (; m < a.L; ++m) {
-        const int cm = (a.n[m] + 255) >> 8;
+        const int cm = (a.n[m] + 1023) >> 10;
         if (c < cm) break;
         c -= cm;
     }
@@ -124,23 +142,55 @@ __global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chu
         rbar[e] = 2.0f * a.R[(long long)(a.part_base[m] + pl) * slab + (long long)i * a.ldr + u];
     }
     __syncthreads();
-    const int j = (c << 8) + threadIdx.x;
+    const int j = (c << 10) + 4 * threadIdx.x;
     if (j >= a.n[m]) return;
-    const int bj = group_of(a.bound[m], gb, j);
+    // output group of each of the four columns (columns past n_m: the last group; their sums are never stored)
+    int bj[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bj[e] = group_of(a.bound[m], gb, min(j + e, a.n[m] - 1));
+    const bool one_group = bj[0] == bj[3];
     const float* __restrict__ pcol = a.P[m] + (long long)i * a.nL * a.ld[m] + j;
-    double acc[DN_MAX_SPLIT];
+    double acc[DN_MAX_SPLIT][4];
 #pragma unroll
-    for (int x = 0; x < DN_MAX_SPLIT; ++x) acc[x] = 0.0;
+    for (int x = 0; x < DN_MAX_SPLIT; ++x)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[x][e] = 0.0;
+    // rows are padded to a multiple of 4 floats, so a full float4 is always readable
+    if (one_group) {
 #pragma unroll 4
-    for (int u = 0; u < a.nL; ++u) {
-        const double pj = (double)pcol[(long long)u * a.ld[m]];
+        for (int u = 0; u < a.nL; ++u) {
+            const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
 #pragma unroll
-        for (int x = 0; x < DN_MAX_SPLIT; ++x)
-            if (x < ga) acc[x] += pj * (double)rbar[(x * gb + bj) * a.nL + u];
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+                if (x < ga) {
+                    const double w = (double)rbar[(x * gb + bj[0]) * a.nL + u];
+                    acc[x][0] += p4.x * w; acc[x][1] += p4.y * w; acc[x][2] += p4.z * w; acc[x][3] += p4.w * w;
+                }
+        }
+    } else {
+        for (int u = 0; u < a.nL; ++u) {
+            const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
+            const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+            for (int x = 0; x < DN_MAX_SPLIT; ++x)
+                if (x < ga) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[x][e] += (double)pe[e] * (double)rbar[(x * gb + bj[e]) * a.nL + u];
+                }
+        }
     }
 #pragma unroll
     for (int x = 0; x < DN_MAX_SPLIT; ++x)
-        if (x < ga) a.Tp[m][((long long)x * a.s + i) * a.ld[m] + j] = (float)acc[x];
+        if (x < ga) {
+            float* t = a.Tp[m] + ((long long)x * a.s + i) * a.ld[m] + j;
+            if (j + 3 < a.n[m]) {
+                *reinterpret_cast<float4*>(t) = make_float4((float)acc[x][0], (float)acc[x][1], (float)acc[x][2], (float)acc[x][3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (j + e < a.n[m]) t[e] = (float)acc[x][e];
+            }
+        }
 }
 
 // Both passes in one for a split structure when n_L <= NLMAX and the hidden widths fit one work-group: the
