@@ -339,8 +339,22 @@ __global__ __launch_bounds__(256) void bias_colsum_kernel(const BiasSumArgs a) {
     const int j = (chunk - a.first[m]) * 16 + c;
     const int i_lo = sidx * a.k_per_split, i_hi = min(a.s, i_lo + a.k_per_split);
     double acc = 0.0;
-    if (j < a.n[m])
-        for (int i = i_lo + r; i < i_hi; i += 16) acc += (double)a.T0[m][(long long)i * a.ld[m] + j];
+    if (j < a.n[m]) {
+        // eight loads in flight per thread, four partial chains, fixed order
+        const float* __restrict__ col = a.T0[m] + j;
+        const long long st = 16 * a.ld[m];
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        int i = i_lo + r;
+        for (; i + 7 * 16 < i_hi; i += 8 * 16) {
+            const float* p = col + (long long)i * a.ld[m];
+            const float v0 = p[0], v1 = p[st], v2 = p[2 * st], v3 = p[3 * st];
+            const float v4 = p[4 * st], v5 = p[5 * st], v6 = p[6 * st], v7 = p[7 * st];
+            a0 += (double)v0 + (double)v4; a1 += (double)v1 + (double)v5;
+            a2 += (double)v2 + (double)v6; a3 += (double)v3 + (double)v7;
+        }
+        for (; i < i_hi; i += 16) a0 += (double)col[(long long)i * a.ld[m]];
+        acc = (a0 + a1) + (a2 + a3);
+    }
     red[r][c] = acc;
     __syncthreads();
     if (r == 0 && j < a.n[m]) {
