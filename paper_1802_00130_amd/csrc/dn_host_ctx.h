@@ -144,6 +144,10 @@ struct dn_ctx {
     const float* fwd_Y = nullptr;
     int fwd_l = 0;
 
+    // the transposed weights in the workspace are those of the theta saved by the last dn_jacobian_prep
+    // (a gradient at another theta overwrites them; the R-operator product restores them before use)
+    bool wt_of_prep = false;
+
     float* fptr(size_t off) const { return reinterpret_cast<float*>(ws + off); }
     double* dptr(size_t off) const { return reinterpret_cast<double*>(ws + off); }
 };

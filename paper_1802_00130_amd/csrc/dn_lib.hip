@@ -119,6 +119,7 @@ int grad_impl(dn_ctx* c, const float* theta, const float* X, const float* Y, int
               bool have_forward) {
     const int L = c->L, n0 = c->dims[0], nL = c->dims[L];
     if (L >= 2) {
+        c->wt_of_prep = false;
         int rc = transpose_weights(c, theta, 2, L);
         if (rc != DN_OK) return rc;
     }
@@ -235,6 +236,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
         DN_HIP(c, ps.end());
     }
     if (L >= 2) {
+        c->wt_of_prep = false;
         rc = transpose_weights(c, theta, 2, L);
         if (rc != DN_OK) return rc;
     }
@@ -256,6 +258,7 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
     }
     c->s_cur = s;
     c->prepped = true;
+    c->wt_of_prep = true;
     return DN_OK;
 }
 
@@ -496,6 +499,12 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
     if (!c->bound || !c->prepped) return DN_ESTATE;
     const int L = c->L, s = c->s_cur;
     const float* th = c->fptr(c->o_thS);
+    // a gradient evaluated at another theta since dn_jacobian_prep has replaced the transposed weights
+    if (L >= 2 && !c->wt_of_prep) {
+        int rc = transpose_weights(c, th, 2, L);
+        if (rc != DN_OK) return rc;
+        c->wt_of_prep = true;
+    }
     // 1. inner sums over t for every layer, Q^m = Z^{m-1} V^m + vb^m; layer 1's result is at once the
     //    derivative of z^1 along v:  zdot^1 = sigma'(s^1) * Q^1
     {

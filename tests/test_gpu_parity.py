@@ -230,6 +230,26 @@ def test_product_without_stored_blocks(wl):
     assert rel_l2(a.cpu().numpy(), b.cpu().numpy()) <= TOL
 
 
+def test_products_keep_the_prepared_theta_after_a_gradient_elsewhere():
+    """Both products belong to the theta handed to dn_jacobian_prep.  A gradient evaluated afterwards at another
+    theta (it shares workspace buffers with the products, the transposed weights among them) changes neither."""
+    cfg = dn_inputs.custom((23, 70, 90, 40, 11), l=150, s=60, C=5.0, seed=31)
+    w = Workload(cfg)
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    other = torch.from_numpy(dn_inputs.make_theta(dn_inputs.custom(cfg.dims, l=cfg.l, s=cfg.s, C=cfg.C, seed=32))).to("cuda:0")
+    assert not torch.equal(other, w.dtheta)
+    dn.dn_grad(w.ctx, other, w.dX, w.dY, w.empty())
+    v = dn_inputs.make_probe(cfg, 2)
+    ref = w.oracle_matvec(v)
+    a, b = w.empty(), w.empty()
+    for _ in range(2):
+        dn.dn_gn_matvec_rop(w.ctx, w.dev(v), a)
+        dn.dn_gn_matvec(w.ctx, w.dev(v), b, dn.DN_FULL)
+        assert rel_l2(a.cpu().numpy(), ref) <= TOL
+        assert rel_l2(b.cpu().numpy(), ref) <= TOL
+    w.ctx.close()
+
+
 def test_subsample_edge_cases():
     """Repeated row ids count twice (the product is a plain sum over the list), a subsample of one row, the
     subsample equal to all rows, and s below s_max after a larger one (the workspace keeps no stale rows)."""
