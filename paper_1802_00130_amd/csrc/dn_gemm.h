@@ -270,7 +270,7 @@ struct TileFetch {
 
     // Slots of mode 4 carry the values of some other, valid row.  They only ever feed output rows
     // (or columns) beyond M (or N), which the epilogue never writes, so they need no zeroing.
-    __device__ __forceinline__ void store(const Addr& a, float* lds, int tid) const {
+    __device__ __forceinline__ void store(const Addr&, float* lds, int tid) const {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) *reinterpret_cast<float4*>(lds + lds_offset(tid + i * NT)) = v[i];
     }
