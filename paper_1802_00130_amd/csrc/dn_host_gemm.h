@@ -82,6 +82,21 @@ hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
     int kmax = 0;
     for (int i = 0; i < g.nprob; ++i) kmax = std::max(kmax, g.p[i].K);
     if (kmax <= 1024) return launch_gemm_t<64, 64, 16, 2, LA, LB, CLS>(g, st);
+    // long sums over K-contiguous operands: K-tiles of 32, two in flight (half the barriers per flop;
+    // 50000 x 1000 x 3072: 121 -> 127 TFLOP/s, 60000 x 4096 x 4096: 125 -> 132, 120000 x 2000 x 2000: 120 -> 122;
+    // no gain at K = 1000 and a loss below that, and a large loss with the transposing loads)
+    if (LA == KC && LB == KC && splits == 1) {
+        long long heaviest = -1;
+        int k_heavy = 0;
+        for (int i = 0; i < g.nprob; ++i) {
+            const long long w = (long long)g.p[i].tiles_m * g.p[i].tiles_n * g.p[i].K;
+            if (w > heaviest) { heaviest = w; k_heavy = g.p[i].K; }
+        }
+        if (k_heavy >= 2000) {
+            finalize_group(g, 64, 64, 32, splits);
+            return launch_gemm_t<64, 64, 32, 2, LA, LB, CLS>(g, st);
+        }
+    }
     return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS>(g, st);
 }
 
