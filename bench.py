@@ -13,7 +13,10 @@ configuration's CG iteration count.  Prints ONE JSON line:
                its mean duration, measured with HIP events inside the same timed steps
   cpu_baseline the fp64 oracle's product rate on the host cores, on the same workload
 
-python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+  extras       (--extras only, measured after the timed steps) partition-mode product and CG, the product
+               without stored blocks, and whole Newton iterations
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--extras]
 """
 from __future__ import annotations
 
@@ -116,6 +119,9 @@ def main():
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain copy kernel of known size (dense copy of stored block P^1) so that "
                          "a counter run can be scaled by what the same counter reads for that copy")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed steps also time the rows beyond the headline path (partition-mode product "
+                         "and CG, product without stored blocks, whole Newton iterations) into an \"extras\" object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -211,6 +217,42 @@ def main():
     torch.cuda.synchronize()
     bracket_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
 
+    extras = None
+    if args.extras:
+        def timed(fn, reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        # split structure 1-2-...-2-1: every hidden layer in two groups (Section 3.1), as in the paper's runs
+        split = tuple(1 if m in (0, cfg.L) else 2 for m in range(cfg.L + 1))
+        nparts = ctx.set_split(split)
+        extras = {"split": "-".join(map(str, split)), "partitions": nparts}
+        extras["matvec_partition_ms"] = timed(lambda: dn.dn_gn_matvec(ctx, dv, out, dn.DN_PARTITION), R)
+        extras["cg_partition_ms_per_iteration"] = timed(
+            lambda: dn.dn_cg(ctx, g, cfg.lam, 0.0, cfg.cg_iters, dn.DN_PARTITION, d), 1) / cfg.cg_iters
+        extras["matvec_rop_ms"] = timed(lambda: dn.dn_gn_matvec_rop(ctx, dv, out), R)
+        # outer iterations (Section 4.5) from the initial point: lambda carried over, forward pass of the
+        # accepted line-search point reused by the next gradient
+        th, dprev, lam = dtheta.clone(), torch.zeros_like(dtheta), cfg.lam
+        iters, cg_total = 4, 0
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for k in range(iters):
+            st = dn.dn_newton_step(ctx, th, dX, dY, dS, dprev, lam, cfg.cg_iters, reuse_forward=(k > 0))
+            lam = st["lam"]
+            cg_total += st["cg_iters"]
+        torch.cuda.synchronize()
+        extras["newton_ms_per_iteration"] = (time.perf_counter() - t1) * 1000.0 / iters
+        extras["newton_cg_iterations"] = cg_total / iters
+        extras["newton_f_last"] = st["f_new"]
+
     phase_ms = {p: 0.0 for p in phases}
     for evs in events:
         for i, p in enumerate(phases):
@@ -249,6 +291,8 @@ def main():
         "warmup_avg_kernel_ms": warm_kernel_ms,
         "roofline": roofline,
     }
+    if extras is not None:
+        res["extras"] = extras
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, X, theta, S)
     print(json.dumps(res))
