@@ -102,10 +102,10 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync", "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit", "dn_sync_status",
-    "dn_profile_enable",
-    "dn_profile_select",
-    "dn_profile_reset", "dn_profile_num_classes", "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
+    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync",
+    "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit",
+    "dn_sync_status", "dn_profile_enable", "dn_profile_select", "dn_profile_reset", "dn_profile_num_classes",
+    "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
 )
 
 
