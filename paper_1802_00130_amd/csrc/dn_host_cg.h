@@ -58,17 +58,18 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
     };
     int iters = 0;
     bool active = any_active(hst);
+    if (part && active) {
+        // p_0 in the theta layout; afterwards every update of p writes both layouts
+        hipLaunchKernelGGL(perm_scatter_kernel, dim3(vgrid), dim3(256), 0, c->stream, p, perm, c->fptr(c->o_ptheta),
+                           c->n);
+        DN_HIP(c, hipGetLastError());
+    }
     while (iters < max_iter && active) {
         int rc;
         if (part) {
-            hipLaunchKernelGGL(perm_scatter_kernel, dim3(vgrid), dim3(256), 0, c->stream, p, perm, c->fptr(c->o_ptheta),
-                               c->n);
-            DN_HIP(c, hipGetLastError());
+            // the result stays in the theta layout; the inner-product kernel below fetches it through perm
             rc = gn_matvec(c, c->fptr(c->o_ptheta), c->fptr(c->o_qtheta), mode);
             if (rc != DN_OK) return rc;
-            hipLaunchKernelGGL(perm_gather_kernel, dim3(vgrid), dim3(256), 0, c->stream, c->fptr(c->o_qtheta), perm, q,
-                               c->n, 1.0f);
-            DN_HIP(c, hipGetLastError());
         } else {
             // the fold at the end of the product also leaves the partial sums of p^T (G + lambda I) p
             rc = gn_matvec(c, p, q, mode, part1, (float)lambda);
@@ -80,14 +81,19 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
             ProfScope ps(c, KC_CG_VEC);
             DN_HIP(c, ps.err);
             if (part) {
-                hipLaunchKernelGGL(cg_dot_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda, part1);
+                hipLaunchKernelGGL(cg_dot_gather_kernel, dim3(grid), dim3(256), 0, c->stream, sg, p, q, (float)lambda,
+                                   part1, perm, c->fptr(c->o_qtheta));
                 DN_HIP(c, hipGetLastError());
             }
             hipLaunchKernelGGL(cg_update_dr_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, part1, p, q,
                                (float)lambda, d_cg, r, part2);
             DN_HIP(c, hipGetLastError());
-            hipLaunchKernelGGL(cg_update_p_kernel, dim3(grid), dim3(256), 0, c->stream, sg, cur, nxt, part2,
-                               sigma * sigma, r, p);
+            if (part)
+                hipLaunchKernelGGL(cg_update_p_kernel<true>, dim3(grid), dim3(256), 0, c->stream, sg, cur, nxt, part2,
+                                   sigma * sigma, r, p, perm, c->fptr(c->o_ptheta));
+            else
+                hipLaunchKernelGGL(cg_update_p_kernel<false>, dim3(grid), dim3(256), 0, c->stream, sg, cur, nxt, part2,
+                                   sigma * sigma, r, p, (const int*)nullptr, (float*)nullptr);
             DN_HIP(c, hipGetLastError());
             DN_HIP(c, ps.end());
         }

@@ -410,7 +410,7 @@ void build_segs(const dn_ctx* c, int mode, CgSegs& sg) {
     }
     sg.cb[sg.nseg] = b;
     // where the partial sums of p^T A p come from: the fold of the product (full and per-layer systems: its
-    // work-groups are grouped by layer), or cg_dot_kernel on this grid (partitions)
+    // work-groups are grouped by layer), or cg_dot_gather_kernel on this grid (partitions)
     if (mode == DN_PARTITION) {
         for (int k = 0; k <= sg.nseg; ++k) sg.pb[k] = sg.cb[k];
     } else {

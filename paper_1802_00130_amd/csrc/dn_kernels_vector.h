@@ -175,25 +175,34 @@ __global__ __launch_bounds__(256) void cg_init_state_kernel(const CgSegs sg, con
     }
 }
 
-// partial p^T (q + lambda p)
-__global__ __launch_bounds__(256) void cg_dot_kernel(const CgSegs sg, const float* __restrict__ p,
-                                                     const float* __restrict__ q, float lambda,
-                                                     double* __restrict__ partials) {
+// Partitions only (the other modes take these partial sums from the fold of the product): partial
+// p^T (q + lambda p), with q fetched from the product's result in the theta layout, q[e] = q_theta[perm[e]],
+// and left in q for the update that follows.
+__global__ __launch_bounds__(256) void cg_dot_gather_kernel(const CgSegs sg, const float* __restrict__ p,
+                                                            float* __restrict__ q, float lambda,
+                                                            double* __restrict__ partials,
+                                                            const int* __restrict__ perm,
+                                                            const float* __restrict__ q_theta) {
     __shared__ double red[4];
     int seg; long long lo, hi;
     cg_locate(sg, seg, lo, hi);
     double acc = 0.0;
     cg_sweep(lo, hi,
              [&](long long e) {
-                 const f32x4v pe = ld4(p + e), qe = ld4(q + e);
+                 const f32x4v pe = ld4(p + e);
+                 f32x4v qe;
+#pragma unroll
+                 for (int k = 0; k < 4; ++k) qe[k] = q_theta[perm[e + k]];
+                 st4(q + e, qe);
                  double s4[4];
 #pragma unroll
                  for (int k = 0; k < 4; ++k) s4[k] = (double)pe[k] * (double)(qe[k] + lambda * pe[k]);
                  acc += (s4[0] + s4[1]) + (s4[2] + s4[3]);
              },
              [&](long long e) {
-                 const float pe = p[e];
-                 acc += (double)pe * (double)(q[e] + lambda * pe);
+                 const float pe = p[e], qe = q_theta[perm[e]];
+                 q[e] = qe;
+                 acc += (double)pe * (double)(qe + lambda * pe);
              });
     acc = block_sum_d(acc, red);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
@@ -240,11 +249,15 @@ __global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, cons
     if (threadIdx.x == 0) rr_partials[blockIdx.x] = acc;
 }
 
-// rho' = r^T r;  stop test ||r|| <= sigma ||g||;  beta = rho'/rho;  p = r + beta p
+// rho' = r^T r;  stop test ||r|| <= sigma ||g||;  beta = rho'/rho;  p = r + beta p.
+// SCATTER: the new p also goes to p_theta[perm[e]], the theta layout the next product reads (a segment that has
+// stopped writes nothing: its p, and with it p_theta, stay as they are).
+template <bool SCATTER>
 __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const CgState* __restrict__ st_cur,
                                                           CgState* __restrict__ st_next,
                                                           const double* __restrict__ rr_partials, double sigma2,
-                                                          const float* __restrict__ r, float* __restrict__ p) {
+                                                          const float* __restrict__ r, float* __restrict__ p,
+                                                          const int* __restrict__ perm, float* __restrict__ p_theta) {
     __shared__ double red[4];
     int seg; long long lo, hi;
     cg_locate(sg, seg, lo, hi);
@@ -265,8 +278,16 @@ __global__ __launch_bounds__(256) void cg_update_p_kernel(const CgSegs sg, const
 #pragma unroll
                  for (int k = 0; k < 4; ++k) pe[k] = re[k] + beta * pe[k];
                  st4(p + e, pe);
+                 if (SCATTER) {
+#pragma unroll
+                     for (int k = 0; k < 4; ++k) p_theta[perm[e + k]] = pe[k];
+                 }
              },
-             [&](long long e) { p[e] = r[e] + beta * p[e]; });
+             [&](long long e) {
+                 const float pe = r[e] + beta * p[e];
+                 p[e] = pe;
+                 if (SCATTER) p_theta[perm[e]] = pe;
+             });
 }
 
 // ---------------------------------------------------------------------------------------------
