@@ -105,3 +105,13 @@ def test_call_order_and_argument_errors(lib):
     assert lib.dn_strerror(-2).decode() == "workspace too small"
     assert lib.dn_profile_num_classes() >= 10 and lib.dn_profile_class_name(0).decode() == "gemm_forward"
     lib.dn_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message before touching anything (this build is single-GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=60)
+    assert out.returncode == 2 and "ONE GPU" in out.stderr and out.stdout.strip() == ""
