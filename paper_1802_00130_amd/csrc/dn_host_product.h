@@ -478,13 +478,17 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
     // 2. the passes over the stored blocks: one pass when a sample's strips fit one work-group's registers
     //    (as in the other modes), else the general two-pass kernels
     {
+        // strip slots: up to 256 columns of one output group of one layer, from the multiple of four at or
+        // below the group's first column
         int w = 0;
         for (int m = 1; m < L; ++m)
-            for (int cidx = 0; cidx < cdiv(c->dims[m], 256); ++cidx, ++w)
-                if (w < DN_MAX_WSLOTS) {
-                    a.wlayer[w] = m;
-                    a.wcol[w] = cidx;
-                }
+            for (int y = 0; y < c->split[m]; ++y)
+                for (int col = c->gbound[m][y] & ~3; col < c->gbound[m][y + 1]; col += 256, ++w)
+                    if (w < DN_MAX_WSLOTS) {
+                        a.wlayer[w] = m;
+                        a.wcol[w] = col;
+                        a.wgrp[w] = y;
+                    }
         a.nwslots = w;
     }
     const bool fused = L >= 2 && c->stream_passes != 2 &&
@@ -493,14 +497,22 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         ProfScope ps(c, KC_JV_JTV_FUSED);
         DN_HIP(c, ps.err);
         const dim3 grid(s), block(64 * std::min(a.nwslots, 16));
+        a.ga_max = a.gb_max = 1;
+        for (int m = 1; m < L; ++m) {
+            a.ga_max = std::max(a.ga_max, c->split[m - 1]);
+            a.gb_max = std::max(a.gb_max, c->split[m]);
+        }
+        // LDS: partial sums per (strip slot, input group, output), then r per (layer, input group, output group, output)
+        const int nlmax = a.nwslots <= 16 ? (nL <= 4 ? 4 : nL <= 8 ? 8 : nL <= 12 ? 12 : 16) : (nL <= 4 ? 4 : 8);
+        const size_t lds = sizeof(float) * ((size_t)a.nwslots + (size_t)(L - 1) * a.gb_max) * a.ga_max * nlmax;
         if (a.nwslots <= 16) {
-            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 1>), grid, block, 0, c->stream, a);
-            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 1>), grid, block, 0, c->stream, a);
-            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_part_kernel<12, 1>), grid, block, 0, c->stream, a);
-            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<16, 1>), grid, block, 0, c->stream, a);
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 1>), grid, block, lds, c->stream, a);
+            else if (nL <= 8)  hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 1>), grid, block, lds, c->stream, a);
+            else if (nL <= 12) hipLaunchKernelGGL((jv_jtv_fused_part_kernel<12, 1>), grid, block, lds, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<16, 1>), grid, block, lds, c->stream, a);
         } else {
-            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 2>), grid, block, 0, c->stream, a);
-            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 2>), grid, block, 0, c->stream, a);
+            if (nL <= 4)       hipLaunchKernelGGL((jv_jtv_fused_part_kernel<4, 2>), grid, block, lds, c->stream, a);
+            else               hipLaunchKernelGGL((jv_jtv_fused_part_kernel<8, 2>), grid, block, lds, c->stream, a);
         }
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());

@@ -24,10 +24,13 @@ struct PartArgs {
     float* Tp[DN_MAX_LAYERS + 1];                     // T^{m,a}: Tp[m] + a * s * ld[m]
     float* R;                                         // [partitions][s][ldr], hidden layers only
     long long ldr;
-    // single-pass kernel: strip slot k is 256 columns of layer wlayer[k], starting at 256 * wcol[k]
+    // single-pass kernel: strip slot k is up to 256 columns of output group wgrp[k] of layer wlayer[k], starting
+    // at column wcol[k] (a multiple of four)
     int nwslots;
     int wlayer[DN_MAX_WSLOTS];
     int wcol[DN_MAX_WSLOTS];
+    int wgrp[DN_MAX_WSLOTS];
+    int ga_max, gb_max;                               // largest split[m-1] and split[m] over the hidden layers m
 };
 
 __device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
@@ -194,49 +197,52 @@ __global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chu
 }
 
 // Both passes in one for a split structure when n_L <= NLMAX and the hidden widths fit one work-group: the
-// strips of P^m_i stay in registers as in jv_jtv_fused_kernel; per input group x the partial sums are kept
-// apart by the output group of each column, and the transposed product picks, column by column, the r of
-// that column's partition.  One HBM read of the stored blocks per product.
+// strips of P^m_i stay in registers as in jv_jtv_fused_kernel.  A strip slot is up to 256 columns of ONE output
+// group of one layer (it starts at the multiple of four at or below the group's first column; columns outside
+// the group are masked), so the sums of a wave belong to one partition per input group x and need no per-column
+// selection: the kernel is bound by vector instruction issue, not by memory, and per-column selects in a
+// layer-wide strip made it 2.3 times slower than the kernel of the other modes.  One HBM read of the stored
+// blocks per product; all input groups go through each stage together (two barriers in all).
+// Dynamic LDS: part[slot][x][u] (nwslots * ga_max * NLMAX floats), then rb[layer-1][x][y][u].
 template <int NLMAX, int CH>
 __global__ __launch_bounds__(1024) void jv_jtv_fused_part_kernel(const PartArgs a) {
-    __shared__ float part[DN_MAX_WSLOTS][DN_MAX_SPLIT][NLMAX];          // [slot][output group][u], one x at a time
-    __shared__ float rb[DN_MAX_LAYERS][DN_MAX_SPLIT][NLMAX];            // [layer][output group][u], one x at a time
+    extern __shared__ float part_lds[];
+    const int gx = a.ga_max, gy = a.gb_max;
+    float* part = part_lds;
+    float* rb = part_lds + a.nwslots * gx * NLMAX;
     const int i = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int nwaves = blockDim.x >> 6;
-    int m[CH], j[CH], bj[CH][4], ylo[CH], yhi[CH];
-    bool live[CH];
+    int m[CH], j[CH], yg[CH];
+    bool live[CH], ok[CH][4];
     float4 p[CH][NLMAX];
-    int gamax = 1;
-    for (int mm = 1; mm < a.L; ++mm) gamax = max(gamax, a.split[mm - 1]);
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) {
         const int slot = wave + ch * nwaves;
         const bool have = slot < a.nwslots;
         m[ch] = have ? a.wlayer[slot] : 1;
-        j[ch] = have ? 4 * (64 * a.wcol[slot] + lane) : 0;
-        live[ch] = have && j[ch] < a.n[m[ch]];
-        {
-            // output groups of the first and last column of this strip slot (same for all lanes)
-            const int c0 = have ? 256 * a.wcol[slot] : 0;
-            ylo[ch] = group_of(a.bound[m[ch]], a.split[m[ch]], c0);
-            yhi[ch] = group_of(a.bound[m[ch]], a.split[m[ch]], min(c0 + 255, a.n[m[ch]] - 1));
-        }
+        yg[ch] = have ? a.wgrp[slot] : 0;
+        j[ch] = have ? a.wcol[slot] + 4 * lane : 0;
+        const int lo = a.bound[m[ch]][yg[ch]], hi = a.bound[m[ch]][yg[ch] + 1];
+        live[ch] = have && j[ch] < hi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ok[ch][e] = live[ch] && j[ch] + e >= lo && j[ch] + e < hi;
         const long long ldm = a.ld[m[ch]];
         const float* __restrict__ pbase = a.P[m[ch]] + (long long)i * a.nL * ldm + j[ch];
 #pragma unroll
         for (int u = 0; u < NLMAX; ++u) {
             p[ch][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            // rows are padded to a multiple of four floats: the whole group of four is readable
             if (live[ch] && u < a.nL) p[ch][u] = *reinterpret_cast<const float4*>(pbase + (long long)u * ldm);
         }
-        // output group of each of the four columns; -1 for padding columns (and their P values cleared)
-        const int rem = live[ch] ? a.n[m[ch]] - j[ch] : 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) bj[ch][e] = e < rem ? group_of(a.bound[m[ch]], a.split[m[ch]], j[ch] + e) : -1;
-        if (rem < 4) {
+        if (!(ok[ch][0] && ok[ch][1] && ok[ch][2] && ok[ch][3])) {
+            // columns of a neighbouring group, or padding: out of the sums
 #pragma unroll
             for (int u = 0; u < NLMAX; ++u) {
-                p[ch][u].w = 0.f; if (rem < 3) p[ch][u].z = 0.f; if (rem < 2) p[ch][u].y = 0.f; if (rem < 1) p[ch][u].x = 0.f;
+                if (!ok[ch][0]) p[ch][u].x = 0.f;
+                if (!ok[ch][1]) p[ch][u].y = 0.f;
+                if (!ok[ch][2]) p[ch][u].z = 0.f;
+                if (!ok[ch][3]) p[ch][u].w = 0.f;
             }
         }
     }
@@ -246,71 +252,72 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_part_kernel(const PartArgs 
             const long long e = ((long long)x * a.s + i) * a.ld[a.L] + u;
             a.Tp[a.L][e] = 2.0f * a.Qp[a.L][e];
         }
-    for (int x = 0; x < gamax; ++x) {
-        // ---- partial sums of this input group, kept apart by output group -------------------------
+    // ---- partial sums of the strip for every input group x ---------------------------------------------
 #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            const int slot = wave + ch * nwaves;
-            const bool on = live[ch] && x < a.split[m[ch] - 1];
-            float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (on) q4 = *reinterpret_cast<const float4*>(a.Qp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch]);
-            // padding columns of Q are never written
-            if (bj[ch][0] < 0) q4.x = 0.f;
-            if (bj[ch][1] < 0) q4.y = 0.f;
-            if (bj[ch][2] < 0) q4.z = 0.f;
-            if (bj[ch][3] < 0) q4.w = 0.f;
-#pragma unroll
-            for (int u = 0; u < NLMAX; ++u) {
-                if (u < a.nL) {
-                    const float t0 = p[ch][u].x * q4.x, t1 = p[ch][u].y * q4.y, t2 = p[ch][u].z * q4.z,
-                                t3 = p[ch][u].w * q4.w;
-#pragma unroll
-                    for (int y = 0; y < DN_MAX_SPLIT; ++y) {
-                        // only the output groups that this strip's 256 columns touch need a reduction (uniform
-                        // in the wave); the others get a plain zero
-                        float v = 0.f;
-                        if (y >= ylo[ch] && y <= yhi[ch]) {
-                            v = (bj[ch][0] == y ? t0 : 0.f) + (bj[ch][1] == y ? t1 : 0.f) +
-                                (bj[ch][2] == y ? t2 : 0.f) + (bj[ch][3] == y ? t3 : 0.f);
-                            v = wave_sum_to_lane63(v);
-                        }
-                        if (lane == 63 && slot < a.nwslots) part[slot][y][u] = v;
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        // ---- r of every partition (layer, x, y), doubled: B = 2I ----------------------------------
-        for (int e = threadIdx.x; e < (a.L - 1) * DN_MAX_SPLIT * NLMAX; e += blockDim.x) {
-            const int u = e % NLMAX, y = (e / NLMAX) % DN_MAX_SPLIT, mm = e / (NLMAX * DN_MAX_SPLIT) + 1;
-            float rsum = 0.f;
-            for (int w = 0; w < a.nwslots; ++w)
-                if (a.wlayer[w] == mm) rsum += part[w][y][u];
-            rb[mm][y][u] = 2.0f * rsum;
-        }
-        __syncthreads();
-        // ---- transposed product: column j takes the r of its own partition -------------------------
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            if (live[ch] && x < a.split[m[ch] - 1]) {
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                const int y0 = bj[ch][0];
+    for (int ch = 0; ch < CH; ++ch) {
+        const int slot = wave + ch * nwaves;
+        if (slot < a.nwslots) {                         // uniform in the wave
+            const int ga = a.split[m[ch] - 1];
+            for (int x = 0; x < ga; ++x) {
+                float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (live[ch])
+                    q4 = *reinterpret_cast<const float4*>(a.Qp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch]);
+                // padding columns of Q are never written (and the masked P is zero there: keep 0 * NaN out)
+                if (!ok[ch][0]) q4.x = 0.f;
+                if (!ok[ch][1]) q4.y = 0.f;
+                if (!ok[ch][2]) q4.z = 0.f;
+                if (!ok[ch][3]) q4.w = 0.f;
+                float* dst = part + (slot * gx + x) * NLMAX;
 #pragma unroll
                 for (int u = 0; u < NLMAX; ++u) {
                     if (u < a.nL) {
-                        const float w0 = rb[m[ch]][y0][u];
-                        const float w1 = bj[ch][1] == y0 ? w0 : (bj[ch][1] >= 0 ? rb[m[ch]][bj[ch][1]][u] : 0.f);
-                        const float w2 = bj[ch][2] == y0 ? w0 : (bj[ch][2] >= 0 ? rb[m[ch]][bj[ch][2]][u] : 0.f);
-                        const float w3 = bj[ch][3] == y0 ? w0 : (bj[ch][3] >= 0 ? rb[m[ch]][bj[ch][3]][u] : 0.f);
-                        acc.x += p[ch][u].x * w0; acc.y += p[ch][u].y * w1; acc.z += p[ch][u].z * w2; acc.w += p[ch][u].w * w3;
+                        float v = (p[ch][u].x * q4.x + p[ch][u].y * q4.y) + (p[ch][u].z * q4.z + p[ch][u].w * q4.w);
+                        v = wave_sum_to_lane63(v);
+                        if (lane == 63) dst[u] = v;
                     }
                 }
-                *reinterpret_cast<float4*>(a.Tp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch]) = acc;
             }
         }
-        // part and rb are rewritten for the next input group only after the barrier at the top of its second
-        // stage has been passed by everyone, i.e. after all reads above have been issued and completed
-        __syncthreads();
+    }
+    __syncthreads();
+    // ---- r of every partition (layer, x, y), doubled: B = 2I ------------------------------------------
+    for (int e = threadIdx.x; e < (a.L - 1) * gx * gy * NLMAX; e += blockDim.x) {
+        const int u = e % NLMAX, y = (e / NLMAX) % gy, x = (e / (NLMAX * gy)) % gx, mm = e / (NLMAX * gy * gx) + 1;
+        float rsum = 0.f;
+        if (u < a.nL && x < a.split[mm - 1] && y < a.split[mm])
+            for (int w = 0; w < a.nwslots; ++w)
+                if (a.wlayer[w] == mm && a.wgrp[w] == y) rsum += part[(w * gx + x) * NLMAX + u];
+        rb[e] = 2.0f * rsum;
+    }
+    __syncthreads();
+    // ---- transposed product with the r of the strip's own partition -------------------------------------
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        if (live[ch]) {
+            const int ga = a.split[m[ch] - 1];
+            const bool whole = ok[ch][0] && ok[ch][1] && ok[ch][2] && ok[ch][3];
+            for (int x = 0; x < ga; ++x) {
+                const float* rx = rb + ((((m[ch] - 1) * gx + x) * gy) + yg[ch]) * NLMAX;
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int u = 0; u < NLMAX; ++u) {
+                    if (u < a.nL) {
+                        const float w0 = rx[u];
+                        acc.x += p[ch][u].x * w0; acc.y += p[ch][u].y * w0; acc.z += p[ch][u].z * w0; acc.w += p[ch][u].w * w0;
+                    }
+                }
+                float* t = a.Tp[m[ch]] + ((long long)x * a.s + i) * a.ld[m[ch]] + j[ch];
+                if (whole) {
+                    *reinterpret_cast<float4*>(t) = acc;
+                } else {
+                    // a group boundary inside these four columns: the neighbouring strip writes the others
+                    if (ok[ch][0]) t[0] = acc.x;
+                    if (ok[ch][1]) t[1] = acc.y;
+                    if (ok[ch][2]) t[2] = acc.z;
+                    if (ok[ch][3]) t[3] = acc.w;
+                }
+            }
+        }
     }
 }
 
