@@ -39,9 +39,6 @@ typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 //     writes them to LDS as one 128-bit store in the KC arrangement, so the MFMA side is identical to KC.
 enum OperandLayout { KC = 0, RC = 1, RT = 2 };
 
-// source of the virtual column of ones of an RT operand (read with stride 0)
-__device__ const float dn_ones4[4] = {1.f, 1.f, 1.f, 1.f};
-
 // Epilogue of a problem, applied in this order to every output element (m, n):
 //   x = alpha * acc;  x += bias[n] (if bias);  x += pre[m * ldpre + n] (if pre);  x = 1/(1+exp(-x)) (if sigmoid);
 //   x *= z(1-z) with z = aux[(m / auxdiv) * ldaux + n] (if aux);  x += add[m * ldadd + n] (if add);
@@ -116,31 +113,34 @@ struct TileFetch {
         int mode[PER_THREAD];
         int rem[PER_THREAD];          // RC mode 2: valid rows counted from this slot's first row
         int ones_at[PER_THREAD];      // RC mode 2: position (0..3) of the virtual ones row, else -1
-        long long ldp[PER_THREAD];    // RT: element stride between consecutive k of this slot (0 for the ones row)
+        const float* pk[PER_THREAD][4];   // RT: the four k-consecutive elements of the NEXT tile to be loaded
+        bool ones[PER_THREAD];        // RT: this slot is the virtual row of ones (its LDS row is written once, by the kernel)
         long long ld;
     };
 
+    // k_first: first k of the first tile that will be loaded (RT keeps running pointers: its loads must be
+    // issued tile after tile, in order, which is how the kernel uses them)
     __device__ static __forceinline__ void init(Addr& a, const float* __restrict__ base, long long ld, int row0,
-                                                int rows_total, int ones_row, int tid) {
+                                                int rows_total, int ones_row, int tid, int k_first) {
         a.ld = ld;
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int s = tid + i * NT;
-            a.mode[i] = 0; a.p[i] = base; a.q[i] = 0; a.rem[i] = 0; a.ones_at[i] = -1; a.ldp[i] = ld;
+            a.mode[i] = 0; a.p[i] = base; a.q[i] = 0; a.rem[i] = 0; a.ones_at[i] = -1; a.ones[i] = false;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a.pk[i][e] = base;
             if (LAYOUT == RT) {
                 // slot = (row = s % ROWS, four consecutive k starting at 4 * (s / ROWS))
                 const int row = row0 + s % ROWS;
                 a.q[i] = 4 * (s / ROWS);
                 const int real_rows = ones_row >= 0 ? rows_total - 1 : rows_total;  // rows that exist in memory
-                if (row == ones_row) {
-                    a.p[i] = dn_ones4;
-                    a.ldp[i] = 0;
-                    a.mode[i] = 1;
-                } else {
-                    // rows past the end read the last real row; they only feed outputs that are never stored
-                    a.p[i] = base + (row < real_rows ? row : real_rows - 1);
-                    a.mode[i] = row < real_rows ? 1 : 4;
-                }
+                // rows past the end, and the virtual row of ones, read the last real row: the former only feed
+                // outputs that are never stored, the latter is never stored to LDS (see store_one())
+                const int rr = row < real_rows ? row : real_rows - 1;
+                a.ones[i] = row == ones_row;
+                a.mode[i] = row < real_rows ? 1 : 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a.pk[i][e] = base + (long long)(k_first + a.q[i] + e) * ld + rr;
             } else if (LAYOUT == KC) {
                 const int row = row0 + s / (BK / 4);
                 a.q[i] = 4 * (s % (BK / 4));
@@ -177,15 +177,23 @@ struct TileFetch {
         if (a.rem[i] > 3) x.w = (a.ones_at[i] == 3) ? 1.f : p[3];
     }
 
+    // RT: the slot's four values of the next tile; the pointers move on by one tile (one 64-bit add each,
+    // instead of a 64-bit multiply-add and three adds from scratch per slot and tile)
+    __device__ static __forceinline__ float4 rt_next(Addr& a, int i) {
+        const float4 x = make_float4(*a.pk[i][0], *a.pk[i][1], *a.pk[i][2], *a.pk[i][3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a.pk[i][e] += (long long)BK * a.ld;
+        return x;
+    }
+
     // Tile lies entirely below k_end: no k checks.  Vector loads only assume 4-byte alignment
     // (f32x4u); the compiler picks the widest access the target allows for that.
-    __device__ __forceinline__ void load_full(const Addr& a, int k0) {
+    __device__ __forceinline__ void load_full(Addr& a, int k0) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (LAYOUT == RT) {
-                const float* p = a.p[i] + (long long)(k0 + a.q[i]) * a.ldp[i];
-                x = make_float4(p[0], p[a.ldp[i]], p[2 * a.ldp[i]], p[3 * a.ldp[i]]);
+                x = rt_next(a, i);
             } else if (LAYOUT == KC) {
                 const f32x4u t = *reinterpret_cast<const f32x4u*>(a.p[i] + k0);
                 x = make_float4(t[0], t[1], t[2], t[3]);
@@ -203,10 +211,9 @@ struct TileFetch {
     }
 
     // One slot of a whole tile whose slots are all of mode 1 or 4 (checked once per work-group).
-    __device__ __forceinline__ void load_clean_one(const Addr& a, int k0, int i) {
+    __device__ __forceinline__ void load_clean_one(Addr& a, int k0, int i) {
         if (LAYOUT == RT) {
-            const float* p = a.p[i] + (long long)(k0 + a.q[i]) * a.ldp[i];
-            v[i] = make_float4(p[0], p[a.ldp[i]], p[2 * a.ldp[i]], p[3 * a.ldp[i]]);
+            v[i] = rt_next(a, i);
         } else {
             const float* p = (LAYOUT == KC) ? a.p[i] + k0 : a.p[i] + (long long)(k0 + a.q[i]) * a.ld;
             const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
@@ -214,7 +221,8 @@ struct TileFetch {
         }
     }
 
-    __device__ __forceinline__ void store_one(float* lds, int tid, int i) const {
+    __device__ __forceinline__ void store_one(const Addr& a, float* lds, int tid, int i) const {
+        if (LAYOUT == RT && a.ones[i]) return;      // that LDS row holds ones for good
         *reinterpret_cast<float4*>(lds + lds_offset(tid + i * NT)) = v[i];
     }
 
@@ -232,17 +240,18 @@ struct TileFetch {
     }
 
     // Last, partial K tile: every element is checked against k_end.
-    __device__ __forceinline__ void load_tail(const Addr& a, int k0, int k_end) {
+    __device__ __forceinline__ void load_tail(Addr& a, int k0, int k_end) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
             if (LAYOUT == RT) {
                 const int k = k0 + a.q[i];
-                const float* p = a.p[i] + (long long)k * a.ldp[i];
-                if (k + 0 < k_end) x.x = p[0];
-                if (k + 1 < k_end) x.y = p[a.ldp[i]];
-                if (k + 2 < k_end) x.z = p[2 * a.ldp[i]];
-                if (k + 3 < k_end) x.w = p[3 * a.ldp[i]];
+                if (k + 0 < k_end) x.x = *a.pk[i][0];
+                if (k + 1 < k_end) x.y = *a.pk[i][1];
+                if (k + 2 < k_end) x.z = *a.pk[i][2];
+                if (k + 3 < k_end) x.w = *a.pk[i][3];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a.pk[i][e] += (long long)BK * a.ld;
             } else if (LAYOUT == KC) {
                 const int k = k0 + a.q[i];
                 const float* p = a.p[i] + k0;
@@ -270,9 +279,16 @@ struct TileFetch {
 
     // Slots of mode 4 carry the values of some other, valid row.  They only ever feed output rows
     // (or columns) beyond M (or N), which the epilogue never writes, so they need no zeroing.
-    __device__ __forceinline__ void store(const Addr&, float* lds, int tid) const {
+    __device__ __forceinline__ void store(const Addr& a, float* lds, int tid) const {
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) *reinterpret_cast<float4*>(lds + lds_offset(tid + i * NT)) = v[i];
+        for (int i = 0; i < PER_THREAD; ++i) store_one(a, lds, tid, i);
+    }
+
+    // RT with a virtual row of ones inside this tile: fill that row of an LDS buffer (all threads call this
+    // once per buffer, before the first barrier; the row is never stored to afterwards)
+    __device__ static __forceinline__ void fill_ones_row(float* lds, int local_row, int tid) {
+        if (LAYOUT == RT && local_row >= 0 && local_row < ROWS)
+            for (int k = tid; k < BK; k += NT) lds[local_row * LDS_STRIDE + k] = 1.0f;
     }
 };
 
@@ -375,10 +391,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
 
     typename FetchA::Addr aa;
     typename FetchB::Addr ab;
-    FetchA::init(aa, P.A, P.lda, m0, P.M, -1, tid);
-    FetchB::init(ab, P.B, P.ldb, n0, P.N, ones_row, tid);
+    FetchA::init(aa, P.A, P.lda, m0, P.M, -1, tid, k_begin);
+    FetchB::init(ab, P.B, P.ldb, n0, P.N, ones_row, tid, k_begin);
     FetchA fa[PF];
     FetchB fb[PF];
+    if (LB == RT && ones_row >= 0) {
+        FetchB::fill_ones_row(ldsB[0], ones_row - n0, tid);
+        FetchB::fill_ones_row(ldsB[1], ones_row - n0, tid);
+    }
 
     const int klen = max(k_end - k_begin, 0);
     const int nfull = klen / BK;                    // whole K tiles
@@ -536,8 +556,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
                 const float* lb = ldsB[cur];
                 // memory instruction number `op` of this tile: stores of slot u+1 first, then refills of slot u
                 auto mem_op = [&](int op) {
-                    if (op < NA)               fa[(u + 1) % PF].store_one(ldsA[cur ^ 1], tid, op);
-                    else if (op < NA + NB)     fb[(u + 1) % PF].store_one(ldsB[cur ^ 1], tid, op - NA);
+                    if (op < NA)               fa[(u + 1) % PF].store_one(aa, ldsA[cur ^ 1], tid, op);
+                    else if (op < NA + NB)     fb[(u + 1) % PF].store_one(ab, ldsB[cur ^ 1], tid, op - NA);
                     else if (op < 2 * NA + NB) fa[u].load_clean_one(aa, k0, op - NA - NB);
                     else if (op < NOPS)        fb[u].load_clean_one(ab, k0, op - 2 * NA - NB);
                 };

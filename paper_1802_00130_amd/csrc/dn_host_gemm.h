@@ -67,16 +67,19 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-// 64x64 tiles, K-tile 16, 4 K-tiles in flight (2 for short sums).  The hand-placed schedule is used for
-// launches of at most 4 work-groups per CU and, at every size, when both operands go through the transposing
-// loads (sums over samples); elsewhere the compiler's schedule of the plain loop is as good.
+// 64x64 tiles, K-tile 16, 4 K-tiles in flight (2 for short sums and for sums over samples).  The hand-placed
+// schedule is used for launches of at most 4 work-groups per CU and, at every size, when both operands go through
+// the transposing loads (sums over samples); elsewhere the compiler's schedule of the plain loop is as good.
 // 128x128 tiles (one work-group per CU) were dropped: with the XCD-aware tile walk, 64x64 tiles are as fast or
 // faster at every shape of the path (2048-2000-2000-2000-100: Jacobian sweeps 82.1 -> 71.5 ms, gradient
 // 69.0 -> 61.3 ms; 4096 x 5 - 1000: sweeps 1779 -> 1671 ms, gradient 714 -> 670 ms).
 template <int LA, int LB, int CLS>
 hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
     finalize_group(g, 64, 64, 16, splits);
-    if (g.total_tiles <= 4 * 256 || (LA == RT && LB == RT)) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
+    // sums over samples (both operands through the transposing loads): two K-tiles in flight (measured 4-6 % faster
+    // than four at every shape: 300 x 785 x 3000 in 8 slices 30.0 -> 28.2 us, 1024 x 1024 x 60000 1157 -> 1097 us)
+    if (LA == RT && LB == RT) return launch_gemm_t<64, 64, 16, 2, LA, LB, CLS, true>(g, st);
+    if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
     // short sums (K <= 1024): two K-tiles in flight are enough, and the smaller register footprint lets a fifth
     // work-group onto each CU (60000 x 300 x 300: 119 -> 113 us)
     int kmax = 0;
