@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
     const int ublocks = (a.nL + UB - 1) / UB;
     const int i = blockIdx.x / ublocks;
     const int u0 = (blockIdx.x - i * ublocks) * UB;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const long long slab = (long long)a.s * a.ldr;
     if (u0 + wave >= a.nL) return;
     int urow[RW];
@@ -211,7 +211,9 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_part_kernel(const PartArgs 
     float* part = part_lds;
     float* rb = part_lds + a.nwslots * gx * NLMAX;
     const int i = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wave index as a scalar: everything looked up by strip slot (layer, row stride, base pointers) then
+    // stays in scalar registers instead of being recomputed per lane
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nwaves = blockDim.x >> 6;
     int m[CH], j[CH], yg[CH];
     bool live[CH], ok[CH][4];

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
     const int ublocks = (a.nL + UB - 1) / UB;
     const int i = blockIdx.x / ublocks;
     const int u0 = (blockIdx.x - i * ublocks) * UB;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const long long slab = (long long)a.s * a.ldr;
     for (int uu = wave; uu < UB; uu += 4) {
         const int u = u0 + uu;
@@ -127,7 +127,9 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
     __shared__ float part[DN_MAX_WSLOTS][NLMAX];
     __shared__ float rb[DN_MAX_LAYERS][NLMAX];
     const int i = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wave index as a scalar: everything looked up by strip slot (layer, row stride, base pointers) then
+    // stays in scalar registers instead of being recomputed per lane
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nwaves = blockDim.x >> 6;
     int m[CH], j[CH];
     bool live[CH];
@@ -147,12 +149,13 @@ __global__ __launch_bounds__(1024) void jv_jtv_fused_kernel(const StreamArgs a) 
             const float4 qb = *reinterpret_cast<const float4*>(a.Qb[m[ch]] + (long long)i * ldm + j[ch]);
             q4[ch].x += qb.x; q4[ch].y += qb.y; q4[ch].z += qb.z; q4[ch].w += qb.w;
         }
-        const float* __restrict__ pbase = a.P[m[ch]] + (long long)i * a.nL * ldm + j[ch];
+        // Every lane loads NLMAX rows without predicates (the kernel is bound by instruction issue as much as by
+        // memory): rows past n_L repeat the last one and are never used, lanes past the layer's width read the
+        // strip's first columns and multiply them by q = 0.
+        const float* __restrict__ pbase = a.P[m[ch]] + (long long)i * a.nL * ldm + (live[ch] ? j[ch] : 0);
 #pragma unroll
-        for (int u = 0; u < NLMAX; ++u) {
-            p[ch][u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (live[ch] && u < a.nL) p[ch][u] = *reinterpret_cast<const float4*>(pbase + (long long)u * ldm);
-        }
+        for (int u = 0; u < NLMAX; ++u)
+            p[ch][u] = *reinterpret_cast<const float4*>(pbase + (long long)min(u, a.nL - 1) * ldm);
     }
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) {
