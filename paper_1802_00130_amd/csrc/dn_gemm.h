@@ -65,6 +65,7 @@ struct GemmProblem {
     int b_ones_col;      // 1: column N-1 of op(B) is a virtual column of ones (not read from memory);
                          //    only for a row-contiguous B
     int accumulate;      // 1: the result is added to what C (of the same K-slice) already holds
+    int c_rows_padded;   // 1: C has whole tiles of rows (tiles_m * 64), rows past M are padding that may be written
 };
 
 struct GemmGroup {
@@ -659,8 +660,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
     }
 
     // ---- epilogue: lane holds column n = .. + r and rows 8*(e/4) + 4*h + e%4 of each 32x32 block ----
+    // Tiles of 20-50 K-steps spend a tenth of their time here, so the common cases are kept lean: one 64-bit
+    // pointer per operand and block (row offsets are multiples of the leading dimension, uniform), no row checks
+    // when the whole tile lies inside the matrix (uniform test), and a branch-free body when nothing but alpha
+    // and the bias apply.
     float* __restrict__ Cb = P.C + (long long)split * P.split_stride;
-    const bool plain = !P.sigmoid && !P.aux && !P.add && !P.accumulate && !P.pre;   // uniform: keep the common case branch-free
+    const bool plain = !P.sigmoid && !P.aux && !P.add && !P.accumulate && !P.pre;   // uniform
+    const bool full_rows = m0 + BM <= P.M || P.c_rows_padded;                          // uniform
     const float alpha = P.alpha;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -669,27 +675,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
         const float bias = P.bias ? P.bias[n] : 0.f;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
+            const int mb = m0 + wm0 + i * 32 + 4 * h;            // row of element e = 0
+            const int mleft = P.M - mb;                          // rows from mb on that exist
+            float* __restrict__ cp = Cb + (long long)mb * P.ldc + n;
             if (plain) {
+                if (full_rows) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-                    if (m < P.M) Cb[(long long)m * P.ldc + n] = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
+                    for (int e = 0; e < 16; ++e)
+                        cp[(long long)(8 * (e / 4) + (e % 4)) * P.ldc] = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (8 * (e / 4) + (e % 4) < mleft)
+                            cp[(long long)(8 * (e / 4) + (e % 4)) * P.ldc] = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
                 }
             } else {
+                const float* __restrict__ prep = P.pre ? P.pre + (long long)mb * P.ldpre + n : nullptr;
+                const float* __restrict__ addp = P.add ? P.add + (long long)mb * P.ldadd + n : nullptr;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-                    if (m >= P.M) continue;
+                    const int dm = 8 * (e / 4) + (e % 4);
+                    if (!full_rows && dm >= mleft) continue;
                     float x = alpha * (acc[i][j][e] + acc2[i][j][e]) + bias;
-                    if (P.pre) x += P.pre[(long long)m * P.ldpre + n];
+                    if (prep) x += prep[(long long)dm * P.ldpre];
                     if (P.sigmoid) x = sigmoidf_fast(x);
                     if (P.aux) {
-                        const float z = P.aux[(long long)(m / P.auxdiv) * P.ldaux + n];
+                        const float z = P.aux[(long long)((mb + dm) / P.auxdiv) * P.ldaux + n];
                         x *= z * (1.0f - z);
                     }
-                    if (P.add) x += P.add[(long long)m * P.ldadd + n];
-                    if (P.accumulate) x += Cb[(long long)m * P.ldc + n];
-                    Cb[(long long)m * P.ldc + n] = x;
+                    if (addp) x += addp[(long long)dm * P.ldadd];
+                    if (P.accumulate) x += cp[(long long)dm * P.ldc];
+                    cp[(long long)dm * P.ldc] = x;
                 }
             }
         }

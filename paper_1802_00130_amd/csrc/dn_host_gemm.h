@@ -21,6 +21,10 @@ GemmProblem mk_problem(const float* A, long long lda, const float* B, long long 
     return p;
 }
 
+// Floats of one K-slice of layer m's partial sums over samples: rows padded to whole 64-row tiles, so that the
+// products that write them need no row checks (the fold reads the first n_m rows only).
+long long tn_slice_floats(const dn_ctx* c, int m) { return round_up(c->dims[m], 64) * c->ldw[m]; }
+
 // Fill tile counts and the tile walk.  splits applies to every problem of the group.
 void finalize_group(GemmGroup& g, int BM, int BN, int BK, int splits) {
     int begin = 0;
@@ -143,7 +147,7 @@ TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
     long long off = 0;
     for (int m = 1; m <= c->L; ++m) {
         pl.offset[m] = off;
-        pl.floats[m] = (long long)pl.splits * c->dims[m] * c->ldw[m];
+        pl.floats[m] = (long long)pl.splits * tn_slice_floats(c, m);
         off += round_up(pl.floats[m], 64);
     }
     pl.total = off;

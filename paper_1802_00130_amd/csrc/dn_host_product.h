@@ -88,7 +88,7 @@ int tn_reduce(dn_ctx* c, const TnPlan* plans /* indexed by layer, or one plan fo
         ra.off[m] = c->woff[m];
         ra.W[m] = c->fptr(c->o_tn) + pl.offset[m];
         ra.ldw[m] = c->ldw[m];
-        ra.split_stride[m] = (long long)c->dims[m] * c->ldw[m];
+        ra.split_stride[m] = tn_slice_floats(c, m);
         ra.splits[m] = pl.splits;
         ra.chunks[m] = cdiv(c->dims[m - 1] + 1, 1024);
         ra.items[m] = c->dims[m] * ra.chunks[m];
@@ -368,7 +368,8 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
             p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]), c->ld[m - 1],
                            c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
             p.b_ones_col = 1;
-            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+            p.split_stride = tn_slice_floats(c, m);
+            p.c_rows_padded = 1;
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
@@ -557,7 +558,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
                 GemmProblem& p = g.p[g.nprob++];
                 p = mk_problem(c->fptr(c->o_Tp[m]) + (long long)x * s * c->ld[m], c->ld[m], c->fptr(c->o_ZS[m - 1]) + t0,
                                c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m] + t0, c->ldw[m], c->dims[m], t1 - t0, s);
-                p.split_stride = (long long)c->dims[m] * c->ldw[m];
+                p.split_stride = tn_slice_floats(c, m);
                 if (g.nprob == DN_MAX_GROUP) {
                     const int rc = flush();
                     if (rc != DN_OK) return rc;
@@ -576,6 +577,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             ba.T0[m] = c->fptr(c->o_Tp[m]);
             ba.W[m] = c->fptr(c->o_tn) + pl.offset[m];
             ba.ldw[m] = c->ldw[m];
+            ba.slice[m] = tn_slice_floats(c, m);
             ba.first[m] = chunks;
             chunks += cdiv(c->dims[m], 16);
         }

@@ -334,6 +334,7 @@ struct BiasSumArgs {
     const float* T0[DN_MAX_LAYERS + 1];     // T^{m,0}
     float* W[DN_MAX_LAYERS + 1];            // partial buffer of layer m: [splits][n_m][ldw]
     long long ldw[DN_MAX_LAYERS + 1];
+    long long slice[DN_MAX_LAYERS + 1];     // floats between the K-slices of layer m
     int splits, k_per_split;
     int first[DN_MAX_LAYERS + 2];           // first 16-neuron chunk of layer m
 };
@@ -370,7 +371,7 @@ __global__ __launch_bounds__(256) void bias_colsum_kernel(const BiasSumArgs a) {
         double t = 0.0;
 #pragma unroll
         for (int k = 0; k < 16; ++k) t += red[k][c];
-        a.W[m][(long long)sidx * a.n[m] * a.ldw[m] + (long long)j * a.ldw[m] + a.n[m - 1]] = (float)t;
+        a.W[m][(long long)sidx * a.slice[m] + (long long)j * a.ldw[m] + a.n[m - 1]] = (float)t;
     }
 }
 

@@ -139,7 +139,7 @@ int grad_impl(dn_ctx* c, const float* theta, const float* X, const float* Y, int
         for (int m = 1; m <= L; ++m) {
             plans[m].splits = 1;
             plans[m].k_per_split = (int)round_up(rows_full, kBKmax);
-            plans[m].floats[m] = (long long)c->dims[m] * c->ldw[m];
+            plans[m].floats[m] = tn_slice_floats(c, m);
             plans[m].offset[m] = tn_off;
             tn_off += round_up(plans[m].floats[m], 64);
         }
@@ -167,7 +167,8 @@ int grad_impl(dn_ctx* c, const float* theta, const float* X, const float* Y, int
                 p = mk_problem(delta, c->ld[m], zprev, ldprev, c->fptr(c->o_tn) + plans[m].offset[m], c->ldw[m],
                                c->dims[m], c->dims[m - 1] + 1, rows);
                 p.b_ones_col = 1;
-                p.split_stride = (long long)c->dims[m] * c->ldw[m];
+                p.split_stride = tn_slice_floats(c, m);
+                p.c_rows_padded = 1;
                 p.accumulate = r0 > 0 ? 1 : 0;
                 ProfScope ps(c, KC_GEMM_TN_GRAD);
                 DN_HIP(c, ps.err);
@@ -570,7 +571,8 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
             p = mk_problem(m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]),
                            c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
             p.b_ones_col = 1;
-            p.split_stride = (long long)c->dims[m] * c->ldw[m];
+            p.split_stride = tn_slice_floats(c, m);
+            p.c_rows_padded = 1;
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
