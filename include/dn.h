@@ -72,6 +72,14 @@ size_t dn_num_params(const dn_ctx* ctx);
 size_t dn_workspace_bytes(const dn_ctx* ctx);
 
 /*
+ * Host-only: number of slices into which a product (dn_gn_matvec, dn_cg, dn_gn_matvec_rop) on s stored samples
+ * cuts its sums over samples (Section 4.2's outer sums; each slice writes partial sums to the workspace, which
+ * are folded in a fixed order).  Always >= 1 and always a plan that fits a workspace of dn_workspace_bytes()
+ * for every 1 <= s <= s_max; DN_EINVAL for a null context or s outside that range.
+ */
+int dn_product_slices(const dn_ctx* ctx, int s);
+
+/*
  * Lend the context a device workspace of at least dn_workspace_bytes() bytes, 256-byte
  * aligned, and the HIP stream (hipStream_t passed as void*, NULL = default stream) on which
  * all later work is enqueued.  Invalidates a previous dn_jacobian_prep.

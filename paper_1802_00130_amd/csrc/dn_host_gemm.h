@@ -134,7 +134,8 @@ int pick_splits(int tiles, int K) {
 
 // Plan of the sums over samples  W_m = T^m^T [Z^{m-1}, 1]  for K samples.  grouped: all layers in
 // one launch (product); otherwise one launch per layer (gradient).
-TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
+// force_splits > 0: that many slices instead of the model's choice.
+TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer, int force_splits = 0) {
     TnPlan pl;
     std::memset(&pl, 0, sizeof(pl));
     int tiles = 0;
@@ -142,7 +143,7 @@ TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
         if (!grouped && m != only_layer) continue;
         tiles += cdiv(c->dims[m], 64) * cdiv(c->dims[m - 1] + 1, 64);
     }
-    pl.splits = pick_splits(tiles, K);
+    pl.splits = force_splits > 0 ? force_splits : pick_splits(tiles, K);
     pl.k_per_split = (int)round_up(cdiv(K, pl.splits), kBKmax);
     long long off = 0;
     for (int m = 1; m <= c->L; ++m) {
@@ -151,6 +152,15 @@ TnPlan plan_tn(const dn_ctx* c, int K, bool grouped, int only_layer) {
         off += round_up(pl.floats[m], 64);
     }
     pl.total = off;
+    return pl;
+}
+
+// The product's plan for s samples, with the slice count cut back to what the workspace's partial buffer holds.
+// pick_splits is not monotone in K, so a smaller s than s_max can ask for more slices than the workspace was
+// sized for (layout_workspace scans the counts up to s_max, this is the safety net); one slice always fits.
+TnPlan plan_tn_product(const dn_ctx* c, int s) {
+    TnPlan pl = plan_tn(c, s, true, 0);
+    while (pl.total > c->tn_floats && pl.splits > 1) pl = plan_tn(c, s, true, 0, pl.splits - 1);
     return pl;
 }
 

@@ -358,7 +358,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
         }
     }
     // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1]
-    TnPlan pl = plan_tn(c, s, true, 0);
+    TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
         GemmGroup g;
@@ -538,7 +538,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         DN_HIP(c, ps.end());
     }
     // 3. sums over samples, one product per (layer, input group) into that group's columns; bias sums apart
-    TnPlan pl = plan_tn(c, s, true, 0);
+    TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
         GemmGroup g;

@@ -31,7 +31,12 @@ void layout_workspace(dn_ctx* c) {
     c->o_WT = take(cur, sizeof(float) * (size_t)round_up(c->n, 64));
     c->o_thS = take(cur, sizeof(float) * (size_t)round_up(c->n, 64));
     c->o_R = take(cur, sizeof(float) * (size_t)L * c->s_max * c->ldr);
+    // partial sums over samples: the product's slice count is not monotone in the number of samples, so take the
+    // largest plan of any s <= s_max (scanned with a stride for very large s_max; plan_tn_product cuts a plan
+    // back if a count in between asks for more)
     long long tn = plan_tn(c, c->s_max, true, 0).total;
+    for (int s = 1, stride = std::max(1, c->s_max / 16384); s < c->s_max; s += stride)
+        tn = std::max(tn, plan_tn(c, s, true, 0).total);
     for (int m = 1; m <= L; ++m) tn = std::max(tn, plan_tn(c, c->l_max, false, m).total);
     c->tn_floats = tn;
     c->o_tn = take(cur, sizeof(float) * (size_t)tn);

@@ -70,6 +70,12 @@ size_t dn_num_params(const dn_ctx* c) { return c ? (size_t)c->n : 0; }
 size_t dn_workspace_bytes(const dn_ctx* c) { return c ? c->ws_bytes : 0; }
 int dn_last_hip_error(const dn_ctx* c) { return c ? c->last_hip : 0; }
 
+int dn_product_slices(const dn_ctx* c, int s) {
+    if (!c || s < 1 || s > c->s_max) return DN_EINVAL;
+    const TnPlan pl = plan_tn_product(c, s);
+    return pl.total <= c->tn_floats ? pl.splits : DN_ENOSPC;
+}
+
 int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     if (!c || !d_workspace) return DN_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0) return DN_EINVAL;
@@ -561,7 +567,7 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
         DN_HIP(c, ps.end());
     }
     // 4. sums over samples for every layer, then out = v/C + (2/|S|) * sums
-    TnPlan pl = plan_tn(c, s, true, 0);
+    TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
         GemmGroup g;
