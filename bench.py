@@ -56,7 +56,7 @@ def work_per_launch(cfg, s):
         "gemm_q_matvec": ("mfma", 2.0 * s * wsum),
         "gemm_tn_matvec": ("mfma", 2.0 * s * wsum),
         "jv_jtv_fused": ("hbm", pbytes),
-        "jv_jtv_team": ("hbm", pbytes_streamed),
+        "jv_jtv_band": ("hbm", pbytes_streamed),
         "jv_rows": ("hbm", pbytes_streamed),
         "jtv_cols": ("hbm", pbytes_streamed),
         "tn_reduce": ("hbm", 4.0 * 3 * cfg.n_params),

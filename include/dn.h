@@ -40,7 +40,8 @@ enum {
     DN_ESTATE = -3,   /* call needs a bound workspace / a prior dn_jacobian_prep and there is none */
     DN_EHIP = -4,     /* a HIP runtime call failed; dn_last_hip_error() gives the HIP code */
     DN_ENOMEM = -5,   /* host allocation failed */
-    DN_ETIMEOUT = -6  /* a bounded wait between work-groups of a kernel ran out (see dn_sync_status) */
+    DN_ETIMEOUT = -6  /* a bounded wait between work-groups of a kernel ran out; the products fell back to the
+                         two-pass kernels (see dn_set_spin_limit, dn_sync_status) */
 };
 
 /* mode of dn_gn_matvec and dn_cg */
@@ -228,25 +229,27 @@ int dn_newton_step(dn_ctx* ctx, float* theta, const float* X, const float* Y, in
  * forgets it.  With mode DN_PARTITION dn_gn_matvec applies the diagonal blocks of G^S over these
  * partitions, dn_cg / dn_cg_sync solve the independent systems (resnorm_host then has
  * dn_num_partitions entries), dn_newton_step uses them in its CG.  All groups[m] = 1 is DN_BLOCKDIAG.
- * With n_L <= 16 the stored blocks are read once per product as in the other modes; wider outputs use general
- * two-pass kernels (every hidden layer's block is streamed twice).
+ * The stored blocks are read once per product as in the other modes.
  */
 int dn_set_split(dn_ctx* ctx, const int* groups);
 int dn_num_partitions(const dn_ctx* ctx);
 
 /*
- * Products with n_L > 16 and at least two hidden layers read each stored block ONCE per product by
- * letting a team of work-groups share a sample (the kernel's work-groups wait for each other on
- * counters in device memory; every wait is bounded).  dn_set_stream_passes(ctx, 2) selects the plain
- * two-pass kernels instead (one read for J v, one for J^T), 0 restores the automatic choice.
+ * Products with n_L > 16 read each stored block ONCE per product by letting a team of work-groups share a
+ * sample (the kernel's work-groups exchange partial sums through device memory and wait for each other;
+ * every wait is bounded).  dn_set_stream_passes(ctx, 2) selects the plain two-pass kernels instead (one read
+ * for J v, one for J^T), 0 restores the automatic choice.
  * dn_set_spin_limit sets the number of polls after which such a wait gives up (default 1 << 20, a few
- * seconds); a wait that runs out makes the kernel's work-groups leave, later products do nothing, and
- * the condition is reported by the next call that synchronises (dn_cg, dn_newton_step, dn_sync_status)
- * as DN_ETIMEOUT.  It is cleared by dn_bind.
+ * seconds; it can only run out when the kernel's work-groups cannot all be resident, e.g. beside another
+ * process's kernels).  A wait that runs out makes the kernel's work-groups leave; the two-pass kernels, which
+ * are enqueued behind every single-pass launch and otherwise return at once, then compute the same product, so
+ * results are complete either way.  The next synchronising call notices the condition and the context uses
+ * the two-pass kernels directly until dn_bind; dn_sync_status reports it ONCE as DN_ETIMEOUT (information,
+ * not a failure).
  */
 int dn_set_stream_passes(dn_ctx* ctx, int passes);
 int dn_set_spin_limit(dn_ctx* ctx, unsigned polls);
-/* Wait for all work enqueued so far; DN_OK, DN_ETIMEOUT (see above) or DN_EHIP. */
+/* Wait for all work enqueued so far; DN_OK, DN_ETIMEOUT (once, see above) or DN_EHIP. */
 int dn_sync_status(dn_ctx* ctx);
 
 /*

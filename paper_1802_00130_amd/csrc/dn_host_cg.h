@@ -113,7 +113,7 @@ int cg_run(dn_ctx* c, const float* g, double lambda, double sigma, int max_iter,
     DN_HIP(c, hipStreamSynchronize(c->stream));
     *iters_host = iters;
     for (int k = 0; k < sg.nseg; ++k) resnorm_host[k] = std::sqrt(hst.rho[k]);
-    return team_status(c);
+    return band_status(c);
 }
 
 }  // namespace

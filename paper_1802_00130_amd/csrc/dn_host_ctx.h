@@ -26,11 +26,11 @@ constexpr int kBKmax = 32;
 // tile rows per super-row of the tile walk: 8 x 8 tiles are about what one XCD (32 CUs) holds at a time
 constexpr int kGroupM = 8;
 // most work-groups of 256 threads a launch can have resident on the chip (256 CUs x 2048 threads / 256);
-// sizes the exchange buffers of the team kernel
+// sizes the exchange buffer of the band kernel
 constexpr int kMaxResidentWGs = 2048;
-// 64-bit words in each exchange region of the team kernel: teams x 2 sets x (work-groups per team) x
-// (at most 128 rows per work-group), teams x work-groups <= kMaxResidentWGs
-constexpr long long kTeamExchWords = 2LL * kMaxResidentWGs * 128;
+// 64-bit words of the band kernel's exchange buffer: 2 sets x (teams x slices <= kMaxResidentWGs work-groups) x
+// (at most DN_MAX_SPLIT input groups) x (32 rows per band)
+constexpr long long kBandExchWords = 2LL * kMaxResidentWGs * DN_MAX_SPLIT * 32;
 
 enum KernelClass {
     KC_GEMM_FWD = 0,      // forward layer products (all samples or subsample)
@@ -42,7 +42,7 @@ enum KernelClass {
     KC_JV_JTV_FUSED,      // product: both passes over P, one read
     KC_JV,                // product: P q
     KC_JTV,               // product: P^T r
-    KC_JV_JTV_TEAM,       // product: both passes over P, one read, teams of work-groups
+    KC_JV_JTV_BAND,       // product: both passes over P, one read, teams of work-groups (plus their idle fall-back)
     KC_GEMM_IMPLICIT,     // product: the two small dense products that stand in for block L-1
     KC_GEMM_ROP,          // product without stored blocks: forward-mode and back-propagation sweeps
     KC_TN_REDUCE,         // slice fold + regularisation term
@@ -55,7 +55,7 @@ enum KernelClass {
 
 const char* const kClassNames[KC_COUNT] = {
     "gemm_forward", "gemm_backprop", "gemm_tn_grad", "gemm_jacobian_prep", "gemm_q_matvec", "gemm_tn_matvec",
-    "jv_jtv_fused", "jv_rows", "jtv_cols", "jv_jtv_team", "gemm_implicit_block", "gemm_rop_sweeps", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
+    "jv_jtv_fused", "jv_rows", "jtv_cols", "jv_jtv_band", "gemm_implicit_block", "gemm_rop_sweeps", "tn_reduce", "jac_init", "gather_rows", "loss", "cg_vector"};
 
 inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -97,8 +97,8 @@ struct dn_ctx {
     size_t o_R = 0, o_tn = 0, o_r = 0, o_p = 0, o_q = 0, o_part[3] = {0, 0, 0}, o_state = 0, o_f = 0;
     // outer Newton iteration: gradient, direction, G d, G d_prev, trial point; partial sums of 5 dot products
     size_t o_ng = 0, o_nd = 0, o_nGd = 0, o_nGdb = 0, o_ntheta = 0, o_npart = 0;
-    // team kernel: partial vectors, folded vectors, counters, error word
-    size_t o_texch = 0, o_terr = 0, o_ttp[DN_MAX_LAYERS + 1] = {0};
+    // band kernel: exchange words, error word
+    size_t o_texch = 0, o_terr = 0;
     // split structure (DN_PARTITION): per input group Q^{m,a} / T^{m,a}, per partition r, the index map that
     // lists theta partition by partition, CG vectors in that order and theta-layout operands of the product
     size_t o_Qp[DN_MAX_LAYERS + 1] = {0}, o_Tp[DN_MAX_LAYERS + 1] = {0}, o_Rp = 0, o_perm = 0, o_gperm = 0,
@@ -109,8 +109,6 @@ struct dn_ctx {
     int nparts = 0;
     long long part_off[DN_MAX_SEGS + 1] = {0};   // partition k covers [part_off[k], part_off[k+1]) of the index map
     bool split_set = false;
-    int team_rpt = 0;               // rows per thread of the team kernel for this n_L (0: team kernel not applicable)
-    int team_nrs = 0;               // row slices
     long long tn_floats = 0;
 
     char* ws = nullptr;
@@ -120,13 +118,15 @@ struct dn_ctx {
     int s_cur = 0;
     int last_hip = 0;
     int num_cus = 256;
-    // team kernel (single pass over the stored blocks for n_L > 16)
+    // band kernel (single pass over the stored blocks for n_L > 16)
     int stream_passes = 0;          // 0 automatic, 2 force the two-pass kernels
     unsigned spin_limit = 1u << 20;
-    bool team_clean = false;        // exchange words and error word cleared since the last dn_bind
-    bool team_used = false;
-    unsigned team_seq = 0;          // sequence numbers handed out so far
-    int team_wgs_per_cu = 0;        // resident work-groups per CU of the kernel variant (0: not looked up)
+    bool band_clean = false;        // exchange words and error word cleared since the last dn_bind
+    bool band_used = false;
+    bool band_off = false;          // a wait ran out since the last dn_bind: two-pass kernels from now on
+    bool timeout_unreported = false;   // ... and dn_sync_status has not said so yet
+    unsigned band_seq = 0;          // sequence numbers handed out so far
+    int band_wgs_per_cu[3] = {0, 0, 0};   // resident work-groups per CU of each kernel variant (0: not looked up)
 
     // profiling
     bool prof = false;

@@ -129,91 +129,131 @@ void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
     a.nwslots = w;
 }
 
-// ---- team kernel plumbing ------------------------------------------------------------------
-struct TeamPlan {
+// ---- single pass over the stored blocks for wide outputs: plumbing of jv_jtv_band_kernel ----------------
+// grid of the two-pass kernels when they are enqueued as the fall-back of the band kernel: they walk over their
+// virtual work-groups, and a launch that finds nothing to do should cost next to nothing
+constexpr int kFallbackGrid = 2048;
+
+struct BandPlan {
     bool ok = false;
-    TeamArgs ta;
+    int H = 0, GA = 1;
+    BandArgs ba;
 };
 
-hipError_t plan_team(dn_ctx* c, const StreamArgs& a, TeamPlan& tp) {
-    tp.ok = false;
-    const int L = c->L;
-    if (c->stream_passes == 2 || c->team_rpt == 0) return hipSuccess;
-    if (c->team_wgs_per_cu == 0) {
+// resident work-groups per CU of kernel variant v (0: H = 16, 1: H = 28, 2: H = 16 with input groups)
+hipError_t band_occupancy(dn_ctx* c, int v, int* wgs) {
+    if (c->band_wgs_per_cu[v] == 0) {
         int nb = 0;
-        hipError_t e = c->team_rpt == 16
-                           ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<16, 0, 4>, 256, 0)
-                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_team_kernel<32, 8, 3>, 256, 0);
+        hipError_t e = v == 0   ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_band_kernel<16, 1, 4>, 256, 0)
+                       : v == 1 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_band_kernel<28, 1, 3>, 256, 0)
+                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, jv_jtv_band_kernel<16, DN_MAX_SPLIT, 3>, 256, 0);
         if (e != hipSuccess) return e;
-        c->team_wgs_per_cu = nb >= 1 ? nb : -1;
+        c->band_wgs_per_cu[v] = nb >= 1 ? nb : -1;
     }
-    if (c->team_wgs_per_cu < 1) return hipSuccess;
-    TeamArgs& ta = tp.ta;
-    std::memset(&ta, 0, sizeof(ta));
-    ta.a = a;
-    const int RB = 4 * c->team_rpt;
-    int ncs = 0;
-    for (int m = 1; m + 1 < L; ++m) {
-        ta.slice_begin[m] = ncs;
-        ncs += cdiv(c->dims[m], 256);
-    }
-    const int G = c->team_nrs * ncs;
-    const int resident = std::min(kMaxResidentWGs, c->num_cus * c->team_wgs_per_cu);
-    const int teams = std::min(a.s, resident / G);
-    if (teams < 1) return hipSuccess;
-    ta.G = G;
-    ta.teams = teams;
-    ta.nrs = c->team_nrs;
-    ta.ncs = ncs;
-    ta.ntasks = (RB / 32) * ta.nrs * (a.blockdiag ? (L - 2) : 1);
-    ta.nfolders = std::min(G, ta.ntasks);
-    ta.part = reinterpret_cast<unsigned long long*>(c->ws + c->o_texch);
-    ta.rbar = ta.part + kTeamExchWords;
-    for (int m = 1; m + 1 < L; ++m) ta.tpart[m] = c->team_nrs > 1 ? c->fptr(c->o_ttp[m]) : nullptr;
-    ta.error = reinterpret_cast<unsigned*>(c->ws + c->o_terr);
-    ta.spin_limit = c->spin_limit;
-    tp.ok = true;
+    *wgs = c->band_wgs_per_cu[v];
     return hipSuccess;
 }
 
-hipError_t launch_team(dn_ctx* c, TeamPlan& tp) {
-    TeamArgs& ta = tp.ta;
-    const unsigned per_launch = (unsigned)cdiv(ta.a.s, ta.teams) + 1u;
-    if (!c->team_clean || c->team_seq > 0x7fff0000u) {
+// mode 0 / 1: layers 1..L-2 (block L-1 is applied as dense products around the kernel); mode 2: 1..L-1.
+// Q, T: per layer, the product's temporaries (partition mode: those of the input groups, one after another)
+hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T, BandPlan& bp) {
+    bp.ok = false;
+    const int L = c->L, nL = c->dims[L], s = c->s_cur;
+    if (c->stream_passes == 2 || c->band_off || nL <= 16) return hipSuccess;
+    const int m_hi = mode == DN_PARTITION ? L - 1 : L - 2;
+    if (m_hi < 1) return hipSuccess;
+    BandArgs& ba = bp.ba;
+    std::memset(&ba, 0, sizeof(ba));
+    ba.L = L; ba.s = s; ba.nL = nL; ba.mode = mode;
+    int ncs = 0;
+    bool fits = true;
+    auto add = [&](int m, int j0, int lo, int hi) {
+        if (ncs < DN_MAX_BAND_SLICES) ba.sl[ncs] = BandSlice{m, j0, lo, hi, 0, 0};
+        else fits = false;
+        ++ncs;
+    };
+    for (int m = 1; m <= m_hi; ++m) {
+        ba.ld[m] = c->ld[m];
+        ba.P[m] = c->fptr(c->o_P[m]);
+        ba.Q[m] = Q[m];
+        ba.T[m] = T[m];
+        ba.ga[m] = mode == DN_PARTITION ? c->split[m - 1] : 1;
+        const int groups = mode == DN_PARTITION ? c->split[m] : 1;
+        const int layer_first = ncs;
+        for (int y = 0; y < groups; ++y) {
+            const int glo = mode == DN_PARTITION ? c->gbound[m][y] : 0;
+            const int ghi = mode == DN_PARTITION ? c->gbound[m][y + 1] : c->dims[m];
+            const int first = ncs;
+            for (int j0 = glo & ~3; j0 < ghi; j0 += 1024) add(m, j0, std::max(glo, j0), std::min(ghi, j0 + 1024));
+            // per-layer blocks share their sums over the whole layer (set below), partitions over the group
+            for (int k = first; k < std::min(ncs, DN_MAX_BAND_SLICES); ++k) { ba.sl[k].c_lo = first; ba.sl[k].c_hi = ncs; }
+        }
+        if (mode == DN_BLOCKDIAG)
+            for (int k = layer_first; k < std::min(ncs, DN_MAX_BAND_SLICES); ++k) { ba.sl[k].c_lo = layer_first; ba.sl[k].c_hi = ncs; }
+    }
+    if (!fits) return hipSuccess;
+    if (mode == DN_FULL)
+        for (int k = 0; k < ncs; ++k) { ba.sl[k].c_lo = 0; ba.sl[k].c_hi = ncs; }
+    ba.ld[L] = c->ld[L];
+    ba.Q[L] = Q[L];
+    ba.T[L] = T[L];
+    ba.ga[L] = mode == DN_PARTITION ? c->split[L - 1] : 1;
+    // rows per band: as equal as possible, at most 28 (16 with input groups: more vectors per thread)
+    const int hmax = mode == DN_PARTITION ? 16 : 28;
+    ba.nrs = cdiv(nL, hmax);
+    ba.rps = cdiv(nL, ba.nrs);
+    bp.GA = mode == DN_PARTITION ? DN_MAX_SPLIT : 1;
+    bp.H = ba.rps <= 16 ? 16 : 28;
+    int wgs = 0;
+    hipError_t e = band_occupancy(c, mode == DN_PARTITION ? 2 : (bp.H == 16 ? 0 : 1), &wgs);
+    if (e != hipSuccess) return e;
+    if (wgs < 1) return hipSuccess;
+    const int resident = std::min(kMaxResidentWGs, c->num_cus * wgs);
+    const int teams_max = std::min(s, resident / ncs);
+    if (teams_max < 1) return hipSuccess;
+    // as many teams as fit (measured: fewer teams with an even share of the samples each are no faster)
+    ba.ncs = ncs;
+    ba.teams = teams_max;
+    ba.part = reinterpret_cast<unsigned long long*>(c->ws + c->o_texch);
+    ba.error = reinterpret_cast<unsigned*>(c->ws + c->o_terr);
+    ba.spin_limit = c->spin_limit;
+    bp.ok = true;
+    return hipSuccess;
+}
+
+hipError_t launch_band(dn_ctx* c, BandPlan& bp) {
+    BandArgs& ba = bp.ba;
+    const unsigned per_launch = (unsigned)cdiv(ba.s, ba.teams) * (unsigned)ba.nrs + 1u;
+    if (!c->band_clean || c->band_seq > 0x7fff0000u) {
         // first use after dn_bind (or the sequence numbers are about to wrap): start from a blank slate
-        hipLaunchKernelGGL(team_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ta.part, 2 * kTeamExchWords,
-                           ta.error);
+        hipLaunchKernelGGL(band_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ba.part, kBandExchWords, ba.error);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        c->team_clean = true;
-        c->team_seq = 0;
+        c->band_clean = true;
+        c->band_seq = 0;
     }
-    ta.seq_base = c->team_seq;
-    c->team_seq += per_launch;
-    c->team_used = true;
-    const dim3 grid(ta.teams * ta.G), block(256);
-    if (c->team_rpt == 16) hipLaunchKernelGGL((jv_jtv_team_kernel<16, 0, 4>), grid, block, 0, c->stream, ta);
-    else                   hipLaunchKernelGGL((jv_jtv_team_kernel<32, 8, 3>), grid, block, 0, c->stream, ta);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || ta.nrs == 1) return e;
-    // several row slices: add their partial transposed products
-    for (int m = 1; m + 1 < c->L; ++m) {
-        const long long total4 = (long long)ta.a.s * c->ld[m] / 4;
-        hipLaunchKernelGGL(team_fold_t_kernel, dim3(grid_for(total4, 256 * 4)), dim3(256), 0, c->stream, ta.tpart[m],
-                           c->fptr(c->o_T[m]), ta.nrs, total4);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    ba.seq_base = c->band_seq;
+    c->band_seq += per_launch;
+    c->band_used = true;
+    const dim3 grid(ba.teams * ba.ncs), block(256);
+    if (bp.GA > 1)       hipLaunchKernelGGL((jv_jtv_band_kernel<16, DN_MAX_SPLIT, 3>), grid, block, 0, c->stream, ba);
+    else if (bp.H == 16) hipLaunchKernelGGL((jv_jtv_band_kernel<16, 1, 4>), grid, block, 0, c->stream, ba);
+    else                 hipLaunchKernelGGL((jv_jtv_band_kernel<28, 1, 3>), grid, block, 0, c->stream, ba);
+    return hipGetLastError();
 }
 
-// after a synchronisation: has a wait of the team kernel run out?
-int team_status(dn_ctx* c) {
-    if (!c->team_used) return DN_OK;
+// After a synchronisation: has a wait of the band kernel run out?  The products were completed by the two-pass
+// kernels enqueued behind it; from now on (until dn_bind) the context uses those directly.
+int band_status(dn_ctx* c) {
+    if (!c->band_used || c->band_off) return DN_OK;
     unsigned err = 0;
     DN_HIP(c, hipMemcpyAsync(&err, c->ws + c->o_terr, sizeof(err), hipMemcpyDeviceToHost, c->stream));
     DN_HIP(c, hipStreamSynchronize(c->stream));
-    return err ? DN_ETIMEOUT : DN_OK;
+    if (err) {
+        c->band_off = true;
+        c->timeout_unreported = true;
+    }
+    return DN_OK;
 }
 
 int gn_matvec_part(dn_ctx* c, const float* v, float* out);
@@ -311,30 +351,43 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
             DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 1, c->stream)));
             DN_HIP(c, ps.end());
         }
-        TeamPlan tp;
-        DN_HIP(c, plan_team(c, a, tp));
-        if (tp.ok) {
-            // one read of the stored blocks: teams of work-groups, see jv_jtv_team_kernel
-            ProfScope ps(c, KC_JV_JTV_TEAM);
+        BandPlan bp;
+        {
+            const float* Qv[DN_MAX_LAYERS + 1] = {nullptr};
+            float* Tv[DN_MAX_LAYERS + 1] = {nullptr};
+            for (int m = 1; m <= L; ++m) { Qv[m] = c->fptr(c->o_Q[m]); Tv[m] = c->fptr(c->o_T[m]); }
+            DN_HIP(c, plan_band(c, mode, Qv, Tv, bp));
+        }
+        int chunks = 1;
+        for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
+        constexpr int UB = 16;
+        if (bp.ok) {
+            // one read of the stored blocks: teams of work-groups, see jv_jtv_band_kernel; behind it the two-pass
+            // kernels, which leave at once unless a wait of the band kernel ran out
+            ProfScope ps(c, KC_JV_JTV_BAND);
             DN_HIP(c, ps.err);
-            DN_HIP(c, launch_team(c, tp));
+            DN_HIP(c, launch_band(c, bp));
+            hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(std::min(s * cdiv(nL, UB), kFallbackGrid)), dim3(256), 0, c->stream,
+                               a, bp.ba.error);
+            DN_HIP(c, hipGetLastError());
+            hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)std::min<long long>((long long)s * chunks, kFallbackGrid)),
+                               dim3(256), sizeof(float) * nL, c->stream, a, chunks, bp.ba.error);
+            DN_HIP(c, hipGetLastError());
             DN_HIP(c, ps.end());
         } else {
             {
                 ProfScope ps(c, KC_JV);
                 DN_HIP(c, ps.err);
-                constexpr int UB = 16;
-                hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a);
+                hipLaunchKernelGGL(jv_rows_kernel<UB>, dim3(s * cdiv(nL, UB)), dim3(256), 0, c->stream, a,
+                                   (const unsigned*)nullptr);
                 DN_HIP(c, hipGetLastError());
                 DN_HIP(c, ps.end());
             }
             {
                 ProfScope ps(c, KC_JTV);
                 DN_HIP(c, ps.err);
-                int chunks = 1;
-                for (int m = 1; m + 1 < L; ++m) chunks += cdiv(c->dims[m], 1024);
                 hipLaunchKernelGGL(jtv_cols_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256),
-                                   sizeof(float) * nL, c->stream, a, chunks);
+                                   sizeof(float) * nL, c->stream, a, chunks, (const unsigned*)nullptr);
                 DN_HIP(c, hipGetLastError());
                 DN_HIP(c, ps.end());
             }
@@ -518,24 +571,46 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     } else {
-        if (L >= 2) {
-            ProfScope ps(c, KC_JV);
-            DN_HIP(c, ps.err);
-            hipLaunchKernelGGL((jv_part_kernel<2>), dim3(s * cdiv(nL, 8)), dim3(256), 0, c->stream, a);
-            DN_HIP(c, hipGetLastError());
-            DN_HIP(c, ps.end());
-        }
-        ProfScope ps(c, KC_JTV);
-        DN_HIP(c, ps.err);
         int chunks = 1;
         for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 1024);
         int most = 1;
         for (int m = 1; m < L; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
         const size_t lds = sizeof(float) * (size_t)most * nL;
-        hipLaunchKernelGGL(jtv_part_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256), lds, c->stream, a,
-                           chunks);
-        DN_HIP(c, hipGetLastError());
-        DN_HIP(c, ps.end());
+        BandPlan bp;
+        {
+            const float* Qv[DN_MAX_LAYERS + 1] = {nullptr};
+            float* Tv[DN_MAX_LAYERS + 1] = {nullptr};
+            for (int m = 1; m <= L; ++m) { Qv[m] = c->fptr(c->o_Qp[m]); Tv[m] = c->fptr(c->o_Tp[m]); }
+            DN_HIP(c, plan_band(c, DN_PARTITION, Qv, Tv, bp));
+        }
+        if (bp.ok) {
+            // one read of the stored blocks (teams of work-groups), the two-pass kernels behind it as the fall-back
+            ProfScope ps(c, KC_JV_JTV_BAND);
+            DN_HIP(c, ps.err);
+            DN_HIP(c, launch_band(c, bp));
+            hipLaunchKernelGGL((jv_part_kernel<2>), dim3(std::min(s * cdiv(nL, 8), kFallbackGrid)), dim3(256), 0, c->stream,
+                               a, bp.ba.error);
+            DN_HIP(c, hipGetLastError());
+            hipLaunchKernelGGL(jtv_part_kernel, dim3((unsigned)std::min<long long>((long long)s * chunks, kFallbackGrid)),
+                               dim3(256), lds, c->stream, a, chunks, bp.ba.error);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        } else {
+            if (L >= 2) {
+                ProfScope ps(c, KC_JV);
+                DN_HIP(c, ps.err);
+                hipLaunchKernelGGL((jv_part_kernel<2>), dim3(s * cdiv(nL, 8)), dim3(256), 0, c->stream, a,
+                                   (const unsigned*)nullptr);
+                DN_HIP(c, hipGetLastError());
+                DN_HIP(c, ps.end());
+            }
+            ProfScope ps(c, KC_JTV);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(jtv_part_kernel, dim3((unsigned)((long long)s * chunks)), dim3(256), lds, c->stream, a,
+                               chunks, (const unsigned*)nullptr);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, ps.end());
+        }
     }
     // 3. sums over samples, one product per (layer, input group) into that group's columns; bias sums apart
     TnPlan pl = plan_tn_product(c, s);

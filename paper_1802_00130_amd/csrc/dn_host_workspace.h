@@ -53,18 +53,8 @@ void layout_workspace(dn_ctx* c) {
     c->o_nGdb = take(cur, nvec);
     c->o_ntheta = take(cur, nvec);
     c->o_npart = take(cur, sizeof(double) * 5 * DN_MAX_PARTIALS);
-    // team kernel: exchange words (two regions of kTeamExchWords 64-bit words: partial vectors, folded
-    // vectors) and, with several row slices, the per-slice partial transposed products
-    c->team_rpt = 0;
-    c->team_nrs = 0;
-    if (L >= 3 && c->dims[L] > 16) {
-        c->team_rpt = round_up(c->dims[L], 32) <= 64 ? 16 : 32;
-        c->team_nrs = cdiv(c->dims[L], 4 * c->team_rpt);
-        c->o_texch = take(cur, sizeof(unsigned long long) * 2 * kTeamExchWords);
-        if (c->team_nrs > 1)
-            for (int m = 1; m + 1 < L; ++m)
-                c->o_ttp[m] = take(cur, sizeof(float) * (size_t)c->team_nrs * c->s_max * c->ld[m]);
-    }
+    // band kernel: exchange words (sequence number + value)
+    if (L >= 2 && c->dims[L] > 16) c->o_texch = take(cur, sizeof(unsigned long long) * kBandExchWords);
     c->o_terr = take(cur, 256);
     for (int m = 1; m <= L; ++m) {
         c->o_Qp[m] = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * c->s_max * c->ld[m]);

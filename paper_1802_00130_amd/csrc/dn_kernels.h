@@ -3,6 +3,6 @@
 #include "dn_common.h"
 #include "dn_kernels_dense.h"
 #include "dn_kernels_stream.h"
-#include "dn_kernels_team.h"
+#include "dn_kernels_band.h"
 #include "dn_kernels_vector.h"
 #include "dn_kernels_part.h"

@@ -43,14 +43,18 @@ __device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
 
 // work-group = (sample, block of 8 outputs); each wave takes two rows u of every hidden layer's block
 template <int RW>
-__global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
+__global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a, const unsigned* only_if) {
+    // only_if (nullable): do nothing while that device word is zero (fall-back launch behind a single-pass kernel).
+    // Virtual work-groups: walked with the grid as the stride, so a launch may have fewer work-groups.
+    if (only_if && __hip_atomic_load(only_if, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
     constexpr int UB = 4 * RW;              // rows per work-group: wave w takes rows u0 + w + 4 k, k < RW, together
     const int ublocks = (a.nL + UB - 1) / UB;
-    const int i = blockIdx.x / ublocks;
-    const int u0 = (blockIdx.x - i * ublocks) * UB;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const long long slab = (long long)a.s * a.ldr;
-    if (u0 + wave >= a.nL) return;
+    for (int vb = blockIdx.x; vb < a.s * ublocks; vb += gridDim.x) {
+    const int i = vb / ublocks;
+    const int u0 = (vb - i * ublocks) * UB;
+    if (u0 + wave >= a.nL) continue;
     int urow[RW];
 #pragma unroll
     for (int k = 0; k < RW; ++k) urow[k] = u0 + wave + 4 * k;
@@ -116,12 +120,13 @@ __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a) {
         }
     }
 }
+}
 
 // work-group = (sample, layer, chunk of 1024 columns); four columns per thread.  Layer L: t^{L,a} = 2 q^{L,a}.
-__global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chunks_total) {
-    extern __shared__ float rbar[];          // [ga][gb][nL] of this layer
-    const int i = blockIdx.x / chunks_total;
-    int c = blockIdx.x - i * chunks_total;
+__device__ __forceinline__ void jtv_part_block(const PartArgs& a, int chunks_total, int vb, float* rbar) {
+    // rbar: [ga][gb][nL] of this layer
+    const int i = vb / chunks_total;
+    int c = vb - i * chunks_total;
     int m = 1;
     for (; m < a.L; ++m) {
         const int cm = (a.n[m] + 1023) >> 10;
@@ -194,6 +199,16 @@ __global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chu
                     if (j + e < a.n[m]) t[e] = (float)acc[x][e];
             }
         }
+}
+
+// virtual work-groups and only_if as in jv_part_kernel
+__global__ __launch_bounds__(256) void jtv_part_kernel(const PartArgs a, int chunks_total, const unsigned* only_if) {
+    extern __shared__ float rbar[];
+    if (only_if && __hip_atomic_load(only_if, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
+    for (int vb = blockIdx.x; vb < a.s * chunks_total; vb += gridDim.x) {
+        jtv_part_block(a, chunks_total, vb, rbar);
+        __syncthreads();        // rbar is filled again by the next virtual work-group
+    }
 }
 
 // Both passes in one for a split structure when n_L <= NLMAX and the hidden widths fit one work-group: the

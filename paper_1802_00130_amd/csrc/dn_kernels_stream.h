@@ -36,11 +36,17 @@ struct StreamArgs {
 // dense product (A^L times sigma'-scaled q^{L-1}), whose result is already inside Q[L] (full) or in
 // slab L-2 of R (per-layer).
 // Work-group = (sample, block of UB outputs); each wave reduces whole rows of P.
+// Virtual work-groups: the kernel walks over them with its grid as the stride, so a launch may have fewer
+// work-groups than there are.
+// only_if (nullable): a device word; the kernel does nothing while it is zero (the launch is then the fall-back
+// of a single-pass kernel that raises the word when it could not finish, made with a small grid).
 template <int UB>
-__global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
+__global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a, const unsigned* only_if) {
+    if (only_if && __hip_atomic_load(only_if, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
     const int ublocks = (a.nL + UB - 1) / UB;
-    const int i = blockIdx.x / ublocks;
-    const int u0 = (blockIdx.x - i * ublocks) * UB;
+    for (int vb = blockIdx.x; vb < a.s * ublocks; vb += gridDim.x) {
+    const int i = vb / ublocks;
+    const int u0 = (vb - i * ublocks) * UB;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const long long slab = (long long)a.s * a.ldr;
     for (int uu = wave; uu < UB; uu += 4) {
@@ -74,16 +80,16 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a) {
             else             a.R[(long long)i * a.ldr + u] = (float)((double)qL + tot);
         }
     }
+    }
 }
 
 // J^T, inner sum of Section 4.2 with B = 2I:  t^{m,i}_j = sum_u P^m_i[u][j] * 2 r_i[u]  (m < L),
 // t^{L,i} = 2 r_i.  Stored blocks m <= L-2 and the output layer; t^{L-1} is a small dense product
 // done after this kernel.  Work-group = (sample, layer, chunk of 1024 columns); threads own 4 columns.
-__global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int chunks_total) {
-    extern __shared__ float rbar[];
+__device__ __forceinline__ void jtv_cols_block(const StreamArgs& a, int chunks_total, int vb, float* rbar) {
     // decode (sample, layer, chunk): chunk list is layer-major within a sample
-    const int i = blockIdx.x / chunks_total;
-    int c = blockIdx.x - i * chunks_total;
+    const int i = vb / chunks_total;
+    int c = vb - i * chunks_total;
     int m = 1;
     for (; m + 1 < a.L; ++m) {
         const int cm = (a.n[m] + 1023) >> 10;
@@ -114,6 +120,16 @@ __global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int c
     }
     float* t = a.T[m] + (long long)i * a.ld[m] + j;
     *reinterpret_cast<float4*>(t) = make_float4((float)ax, (float)ay, (float)az, (float)aw);
+}
+
+// virtual work-groups and only_if as in jv_rows_kernel
+__global__ __launch_bounds__(256) void jtv_cols_kernel(const StreamArgs a, int chunks_total, const unsigned* only_if) {
+    extern __shared__ float rbar[];
+    if (only_if && __hip_atomic_load(only_if, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) return;
+    for (int vb = blockIdx.x; vb < a.s * chunks_total; vb += gridDim.x) {
+        jtv_cols_block(a, chunks_total, vb, rbar);
+        __syncthreads();        // rbar is filled again by the next virtual work-group
+    }
 }
 
 // Both passes in one when n_L <= NLMAX and the hidden widths fit one work-group (all hidden layers'

@@ -84,9 +84,11 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->bound = true;
     c->prepped = false;
-    c->team_clean = false;
+    c->band_clean = false;
     c->fwd_valid = false;
-    c->team_used = false;
+    c->band_used = false;
+    c->band_off = false;
+    c->timeout_unreported = false;
     c->split_set = false;
     // size of the chip, for kernels whose grid must be resident all at once (default kept if no device answers)
     int dev = 0, cus = 0;
@@ -479,7 +481,7 @@ int dn_newton_step(dn_ctx* c, float* theta, const float* X, const float* Y, int 
     st->f_new = f_new;
     DN_HIP(c, hipMemcpyAsync(d_prev, d, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c->stream));
     DN_HIP(c, hipStreamSynchronize(c->stream));
-    return team_status(c);
+    return band_status(c);
 }
 
 int dn_set_stream_passes(dn_ctx* c, int passes) {
@@ -498,7 +500,13 @@ int dn_sync_status(dn_ctx* c) {
     if (!c) return DN_EINVAL;
     if (!c->bound) return DN_ESTATE;
     DN_HIP(c, hipStreamSynchronize(c->stream));
-    return team_status(c);
+    const int rc = band_status(c);
+    if (rc != DN_OK) return rc;
+    if (c->timeout_unreported) {
+        c->timeout_unreported = false;
+        return DN_ETIMEOUT;
+    }
+    return DN_OK;
 }
 
 int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {

@@ -13,6 +13,29 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+def block_errors(a, b, dims):
+    """Relative L2 error of every weight block A^m and every bias block b^m of two theta-layout vectors, as a
+    list of (name, error): a whole-vector norm alone would let a percent-level error in a small block pass."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    out = []
+    for m, (w, bo) in enumerate(dn_inputs.layer_offsets(dims), start=1):
+        nw = dims[m - 1] * dims[m]
+        out.append((f"A{m}", rel_l2(a[w:w + nw], b[w:w + nw])))
+        out.append((f"b{m}", rel_l2(a[bo:bo + dims[m]], b[bo:bo + dims[m]])))
+    return out
+
+
+def assert_close_blocks(a, b, dims, tol, what=""):
+    """Whole-vector relative L2 error within tol, and every block's own relative error within tol."""
+    whole = rel_l2(a, b)
+    blocks = block_errors(a, b, dims)
+    worst = max(blocks, key=lambda t: t[1])
+    assert whole <= tol, (what, whole)
+    assert worst[1] <= tol, (what, worst)
+    return whole, worst
+
+
 class Workload:
     def __init__(self, cfg, bias_scale=0.0, rows=None, l_max=None):
         self.cfg = cfg
@@ -45,21 +68,27 @@ class Workload:
         return f(self.theta.astype(np.float64), self.cfg.dims, self.cfg.C, self.XS64, v.astype(np.float64))
 
 
-def cg_fp32_vectors(oracle, theta, dims, C, XS, g, lam, iters):
-    """The oracle's CG (full system) with every vector rounded to fp32 after each update and the step lengths
-    rounded to fp32, products and inner products in fp64: what limits a CG whose vectors are stored in fp32,
-    whatever computes the products.  Test-side arithmetic on top of the oracle's product."""
+def cg_fp32_vectors(oracle, theta, dims, C, XS, g, lam, iters, blockdiag=False):
+    """The oracle's CG (full system, or the per-layer systems) with every vector rounded to fp32 after each update
+    and the step lengths rounded to fp32, products and inner products in fp64: what limits a CG whose vectors are
+    stored in fp32, whatever computes the products.  Test-side arithmetic on top of the oracle's product."""
     f32 = lambda a: a.astype(np.float32).astype(np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    blocks = oracle.block_slices(dims) if blockdiag else [slice(0, g.shape[0])]
+    product = oracle.gn_matvec_blockdiag if blockdiag else oracle.gn_matvec
     d = np.zeros_like(g)
     r = f32(-g)
     p = r.copy()
-    rho = r @ r
+    rho = [r[b] @ r[b] for b in blocks]
     for _ in range(iters):
-        q = f32(oracle.gn_matvec(theta, dims, C, XS, p))
-        alpha = np.float64(np.float32(rho / (p @ (q + lam * p))))
-        d = f32(d + alpha * p)
-        r = f32(r - alpha * f32(q + f32(lam * p)))
-        rho_new = r @ r
-        p = f32(r + np.float64(np.float32(rho_new / rho)) * p)
-        rho = rho_new
+        q = f32(product(theta, dims, C, XS, p))
+        for k, b in enumerate(blocks):
+            if rho[k] == 0.0:
+                continue
+            alpha = np.float64(np.float32(rho[k] / (p[b] @ (q[b] + lam * p[b]))))
+            d[b] = f32(d[b] + alpha * p[b])
+            r[b] = f32(r[b] - alpha * f32(q[b] + f32(lam * p[b])))
+            rho_new = r[b] @ r[b]
+            p[b] = f32(r[b] + np.float64(np.float32(rho_new / rho[k])) * p[b])
+            rho[k] = rho_new
     return d

@@ -7,14 +7,20 @@ workloads keep every decision away from its threshold.  Continuous outcomes: the
 and gets the CG bar, 1e-3 relative L2; everything computed from it inherits that bar on the part it drives:
 theta within 1e-3 of the step length (plus fp32 rounding of theta itself), f(theta + alpha d) within
 1e-4 |f| plus 2e-3 of the change of f over the step, g^T d within 1e-3, d^T G d within 2e-3,
-rho within 1e-2 absolute.  The two "harsh" workloads get 2e-3 for the direction and theta: their tiny,
-badly conditioned systems sit at the edge of what an fp32 recurrence can follow (a CPU emulation of CG with
-its vectors rounded to fp32 differs from the fp64 iterates by 0.9e-3 there after three iterations).
-beta solves a 2x2 system whose entries are linear and quadratic in the CG direction and so carry up to twice
-its error, so its bar is three times the direction's bar times
-that system's condition number after diagonal scaling, (1 + |c|) / (1 - |c|) with c the cosine between the
-CG direction and the previous one in the Gauss-Newton inner product, and it is compared in the scaled
-coordinates (beta_1 sqrt(d^T G d), beta_2 sqrt(dbar^T G dbar)).
+rho within 1e-2 absolute.
+The two "harsh" workloads (saturated start, tiny subsample, weak damping) get a COMPUTED allowance on top of that
+bar.  Their output-layer system is an exact quadratic in a few unknowns that three CG iterations all but solve;
+from there on a recurrence in fp32 only turns rounding noise over, so that block of the CG iterate is the least
+accurate one (up to 3e-4 of its own norm, while the whole vector, dominated by the large steps of the saturated
+hidden layers, stays near 4e-5).  The inner products of the combination step (g^T d, d^T G d) are dominated by
+exactly that block, and the coefficients beta, a ratio of a linear and a quadratic form in d, carry up to three
+times its error into the combined direction.  The test therefore measures, on the device's own gradient, the
+worst per-block error of the device's CG iterate against the oracle's and allows 1e-3 + 3 x that for the
+direction and theta of these two workloads; products (1e-7 in every block) and the gradient (2e-7 in every block)
+are not what limits them.  beta is compared in the scaled coordinates (beta_1 sqrt(d^T G d),
+beta_2 sqrt(dbar^T G dbar)) with the direction's bar times the condition number of the 2x2 system after diagonal
+scaling, (1 + |c|) / (1 - |c|), c the cosine between the CG direction and the previous one in the Gauss-Newton
+inner product.
 A free-running comparison of the objective over the same iterations follows with a looser bar.
 """
 import numpy as np
@@ -24,7 +30,7 @@ import torch
 import dn_inputs
 import paper_1802_00130_amd as dn
 from oracle import dn_oracle as orc
-from tests.gpu_common import Workload, rel_l2
+from tests.gpu_common import Workload, block_errors, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -70,6 +76,23 @@ def test_newton_iterations(name, mode):
         S = _subset(cfg, k)
         th_in = theta.cpu().numpy().astype(np.float64)
         dp_in = d_prev.cpu().numpy().astype(np.float64)
+        tol_d = 1e-3
+        if name.startswith("harsh"):
+            # the CG iterate the step is about to compute (same kernels on the same data: same bits), block by
+            # block against the oracle's iterate from the same right-hand side
+            g_dev_t, d_cg_t = w.empty(), w.empty()
+            dn.dn_grad(w.ctx, theta, w.dX, w.dY, g_dev_t, want_f=False)
+            dn.dn_jacobian_prep(w.ctx, theta, w.dX, torch.from_numpy(S).to("cuda:0"))
+            dn.dn_cg(w.ctx, g_dev_t, lam, 0.0, cg_max, mode, d_cg_t)
+            g_dev = g_dev_t.cpu().numpy().astype(np.float64)
+            d_cg_ref, _, _ = orc.cg(th_in, cfg.dims, cfg.C, X64[S], g_dev, lam, cg_max, sigma=0.0,
+                                    blockdiag=(mode == dn.DN_BLOCKDIAG))
+            e_cg = rel_l2(d_cg_t.cpu().numpy(), d_cg_ref)
+            worst = max(block_errors(d_cg_t.cpu().numpy(), d_cg_ref, cfg.dims), key=lambda t: t[1])
+            print(f"  k={k}: CG iterate on the device's gradient: whole {e_cg:.1e}, worst block {worst[0]} {worst[1]:.1e}",
+                  flush=True)
+            assert e_cg <= 1e-3
+            tol_d = 1e-3 + 3.0 * worst[1]
         out = dn.dn_newton_step(w.ctx, theta, w.dX, w.dY, torch.from_numpy(S).to("cuda:0"), d_prev, lam, cg_max,
                                 sigma=0.0, mode=mode)
         g_ref, _ = orc.grad(th_in, cfg.dims, cfg.C, X64, Y64)
@@ -87,7 +110,6 @@ def test_newton_iterations(name, mode):
               f"f_new {abs(out['f_new'] - ref['f_new']) / abs(ref['f_new']):.1e}, rho {abs(out['rho'] - ref['rho']):.1e}",
               flush=True)
         assert abs(out["f_new"] - ref["f_new"]) <= 1e-4 * abs(ref["f_new"]) + 2e-3 * step
-        tol_d = 2e-3 if name.startswith("harsh") else 1e-3
         assert e_d <= tol_d
         assert e_th <= tol_d * np.linalg.norm(ref["theta"] - th_in) + 1e-6 * np.linalg.norm(ref["theta"])
         if k == 0:
@@ -101,7 +123,7 @@ def test_newton_iterations(name, mode):
             scale2 = np.sqrt([a11, a22])
             e_beta = rel_l2(np.array(out["beta"]) * scale2, np.array(ref["beta"]) * scale2)
             print(f"       beta error {e_beta:.1e}, condition number of the scaled 2x2 system {kappa:.1f}", flush=True)
-            assert e_beta <= 3.0 * tol_d * kappa
+            assert e_beta <= tol_d * kappa
         assert abs(out["gTd"] - ref["gTd"]) <= 1e-3 * abs(ref["gTd"])
         assert abs(out["dGd"] - ref["dGd"]) <= 2e-3 * abs(ref["dGd"])
         assert abs(out["rho"] - ref["rho"]) <= 1e-2

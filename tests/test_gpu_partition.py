@@ -27,6 +27,11 @@ CASES = {
     "mid_1-2-2-1": (lambda: dn_inputs.custom((200, 300, 260, 10), l=900, s=300, C=50.0, seed=78), (1, 2, 2, 1)),
     # more than 16 strip slots: two strips per wave in the single-pass kernel
     "wide_2-3-4-1": (lambda: dn_inputs.custom((14, 2600, 1700, 7), l=40, s=10, C=4.0, seed=79), (2, 3, 4, 1)),
+    # n_L > 16: the single-pass kernel of wide outputs, one to several slices per output group, group bounds that
+    # are no multiples of four, several bands of rows per sample
+    "wide_out_2-3-4-1": (lambda: dn_inputs.custom((14, 2600, 1701, 37), l=40, s=10, C=4.0, seed=80), (2, 3, 4, 1)),
+    "wide_out_3-2-3-4": (lambda: dn_inputs.custom((20, 1030, 45, 130), l=300, s=260, C=4.0, seed=81), (3, 2, 3, 4)),
+    "wide_out_deep": (lambda: dn_inputs.custom((33, 2100, 530, 1200, 100), l=60, s=24, C=9.0, seed=82), (1, 2, 2, 2, 1)),
 }
 
 
