@@ -40,6 +40,7 @@ enum {
     DN_ESTATE = -3,   /* call needs a bound workspace / a prior dn_jacobian_prep and there is none */
     DN_EHIP = -4,     /* a HIP runtime call failed; dn_last_hip_error() gives the HIP code */
     DN_ENOMEM = -5,   /* host allocation failed */
+    DN_ETOOBIG = -7,  /* dn_forward_static: the problem needs more than DN_STATIC_SCRATCH_BYTES of scratch */
     DN_ETIMEOUT = -6  /* a bounded wait between work-groups of a kernel ran out; the products fell back to the
                          two-pass kernels (see dn_set_spin_limit, dn_sync_status) */
 };
@@ -96,6 +97,23 @@ int dn_bind(dn_ctx* ctx, void* d_workspace, size_t bytes, void* hip_stream);
  */
 int dn_forward(dn_ctx* ctx, const float* theta, const float* X, const float* Y, int l,
                double* f_host, float* ZL);
+
+/*
+ * dn_forward for callers that cannot allocate device memory or keep a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same value f (and outputs ZL, nullable) as
+ * dn_forward on a context with l_max >= l, but no context and no workspace: the activations and partial sums
+ * live in a scratch array that is part of the library's device code (DN_STATIC_SCRATCH_BYTES per GPU, held from
+ * the first call on that GPU until the process ends).  The call allocates nothing, on the host or on the device.
+ * dims[0..L], C as in dn_create; theta, X, Y, ZL are device pointers as in dn_forward; the work is enqueued on
+ * hip_stream (hipStream_t as void*, NULL = default stream), which is synchronised before *f_host is written.
+ * The scratch needed is 4 l sum_{m=1..L} roundup4(n_m) bytes plus 17 KB; a problem beyond the limit is rejected
+ * with DN_ETOOBIG before anything is launched (split the rows and add the loss terms, or use dn_forward).
+ * All calls on one GPU share that GPU's scratch: calls that overlap in time on the same GPU race; calls one
+ * after the other need no clean-up in between (the call writes every word of the scratch before it reads it).
+ */
+#define DN_STATIC_SCRATCH_BYTES (32u << 20)
+int dn_forward_static(int L, const int* dims, double C, const float* theta, const float* X, const float* Y, int l,
+                      void* hip_stream, double* f_host, float* ZL);
 
 /*
  * Gradient by back-propagation (Section 2.2, Section 3.4):

@@ -72,6 +72,7 @@ def load_library() -> ctypes.CDLL:
         "dn_product_slices": (i, [vp, i]),
         "dn_bind": (i, [vp, vp, sz, vp]),
         "dn_forward": (i, [vp, vp, vp, vp, i, P(d), vp]),
+        "dn_forward_static": (i, [i, P(i), d, vp, vp, vp, i, vp, P(d), vp]),
         "dn_grad": (i, [vp, vp, vp, vp, i, vp, P(d)]),
         "dn_jacobian_prep": (i, [vp, vp, vp, i, vp, i]),
         "dn_jacobian_read": (i, [vp, i, vp]),
@@ -103,7 +104,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = (
     "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_product_slices", "dn_bind", "dn_forward",
-    "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync",
+    "dn_forward_static", "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync",
     "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit",
     "dn_sync_status", "dn_profile_enable", "dn_profile_select", "dn_profile_reset", "dn_profile_num_classes",
     "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
@@ -220,6 +221,29 @@ def dn_forward(ctx: Context, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tens
     rc = ctx._lib.dn_forward(ctx._h, _dev_f32(theta, "theta", ctx.n), _dev_f32(X, "X", l * ctx.dims[0]),
                              _dev_f32(Y, "Y", l * ctx.dims[-1]), l, ctypes.byref(f), zl)
     ctx._check(rc, "dn_forward")
+    return f.value
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def dn_forward_static(dims: Sequence[int], C: float, theta: torch.Tensor, X: torch.Tensor, Y: torch.Tensor,
+                      ZL: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """f(theta) as dn_forward, through the entry point that allocates nothing (no context, no workspace: the
+    library's fixed scratch).  Raises DnError with code -7 when the problem exceeds that scratch."""
+    lib = load_library()
+    dims = tuple(int(x) for x in dims)
+    l = X.shape[0]
+    n = sum(dims[m - 1] * dims[m] + dims[m] for m in range(1, len(dims)))
+    arr = (ctypes.c_int * len(dims))(*dims)
+    f = ctypes.c_double()
+    zl = 0 if ZL is None else _dev_f32(ZL, "ZL", l * dims[-1])
+    st = stream if stream is not None else torch.cuda.current_stream(X.device)
+    rc = lib.dn_forward_static(len(dims) - 1, arr, float(C), _dev_f32(theta, "theta", n),
+                               _dev_f32(X, "X", l * dims[0]), _dev_f32(Y, "Y", l * dims[-1]), l, st.cuda_stream,
+                               ctypes.byref(f), zl)
+    if rc != 0:
+        raise DnError(rc, "dn_forward_static")
     return f.value
 
 

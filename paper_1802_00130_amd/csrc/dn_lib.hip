@@ -7,32 +7,44 @@
 #include "dn_host_cg.h"
 
 
-// ================================================================================================
-extern "C" {
+// Scratch of dn_forward_static: device memory that exists without any allocation call.  One copy per GPU, at an
+// address of its own on each; host code never uses the array's name as an address, only what hipGetSymbolAddress
+// returned for the device that is current.
+static __device__ __align__(256) unsigned char scratch[DN_STATIC_SCRATCH_BYTES];
 
-const char* dn_strerror(int code) {
-    switch (code) {
-        case DN_OK: return "ok";
-        case DN_EINVAL: return "invalid argument";
-        case DN_ENOSPC: return "workspace too small";
-        case DN_ESTATE: return "call out of order (no workspace bound, or no Jacobian prepared)";
-        case DN_EHIP: return "HIP runtime error";
-        case DN_ENOMEM: return "host allocation failed";
-        case DN_ETIMEOUT: return "a bounded wait between work-groups ran out";
-        default: return "unknown error code";
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of `scratch` on the current device (looked up once per device)
+hipError_t static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
     }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
-int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_max) {
-    if (!out) return DN_EINVAL;
-    *out = nullptr;
-    if (!dims || L < 1 || L > DN_MAX_LAYERS || !(C > 0.0) || l_max < 1 || s_max < 1) return DN_EINVAL;
+bool valid_network(int L, const int* dims, double C) {
+    if (!dims || L < 1 || L > DN_MAX_LAYERS || !(C > 0.0)) return false;
     for (int m = 0; m <= L; ++m)
-        if (dims[m] < 1) return DN_EINVAL;
-    // row counts of the batched sweeps are int: s_max * n_L rows
-    if ((long long)s_max * dims[L] > 0x7fffffffLL) return DN_EINVAL;
-    dn_ctx* c = new (std::nothrow) dn_ctx();
-    if (!c) return DN_ENOMEM;
+        if (dims[m] < 1) return false;
+    return true;
+}
+
+// sizes, strides and theta offsets of the network (Section 2.1); no workspace map yet
+void init_network(dn_ctx* c, int L, const int* dims, double C, int l_max, int s_max) {
     c->L = L;
     c->C = C;
     c->l_max = l_max;
@@ -51,6 +63,36 @@ int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_m
     }
     c->n = o;
     c->ldr = round_up(dims[L], 4);
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char* dn_strerror(int code) {
+    switch (code) {
+        case DN_OK: return "ok";
+        case DN_EINVAL: return "invalid argument";
+        case DN_ENOSPC: return "workspace too small";
+        case DN_ETOOBIG: return "problem exceeds the fixed scratch of the call that allocates nothing";
+        case DN_ESTATE: return "call out of order (no workspace bound, or no Jacobian prepared)";
+        case DN_EHIP: return "HIP runtime error";
+        case DN_ENOMEM: return "host allocation failed";
+        case DN_ETIMEOUT: return "a bounded wait between work-groups ran out";
+        default: return "unknown error code";
+    }
+}
+
+int dn_create(dn_ctx** out, int L, const int* dims, double C, int l_max, int s_max) {
+    if (!out) return DN_EINVAL;
+    *out = nullptr;
+    if (!valid_network(L, dims, C) || l_max < 1 || s_max < 1) return DN_EINVAL;
+    // row counts of the batched sweeps are int: s_max * n_L rows
+    if ((long long)s_max * dims[L] > 0x7fffffffLL) return DN_EINVAL;
+    dn_ctx* c = new (std::nothrow) dn_ctx();
+    if (!c) return DN_ENOMEM;
+    init_network(c, L, dims, C, l_max, s_max);
     layout_workspace(c);
     *out = c;
     return DN_OK;
@@ -115,6 +157,36 @@ int dn_forward(dn_ctx* c, const float* theta, const float* X, const float* Y, in
         if (rc != DN_OK) return rc;
     }
     return DN_OK;
+}
+
+int dn_forward_static(int L, const int* dims, double C, const float* theta, const float* X, const float* Y, int l,
+                      void* hip_stream, double* f_host, float* ZL) {
+    if (!valid_network(L, dims, C) || !theta || !X || !Y || !f_host || l < 1) return DN_EINVAL;
+    // a context on the stack (its containers stay empty: no profiling here), mapped onto the static scratch:
+    // activations of the l rows, the two partial-sum arrays and the result word -- what dn_forward uses of a workspace
+    dn_ctx ctx;
+    dn_ctx* c = &ctx;
+    init_network(c, L, dims, C, l, 1);
+    size_t cur = 0;
+    for (int m = 1; m <= L; ++m) {
+        const unsigned long long bytes = sizeof(float) * (unsigned long long)l * (unsigned long long)c->ld[m];
+        if (bytes > DN_STATIC_SCRATCH_BYTES) return DN_ETOOBIG;
+        c->o_Zall[m] = take(cur, (size_t)bytes);
+        if (cur > DN_STATIC_SCRATCH_BYTES) return DN_ETOOBIG;
+    }
+    for (int k = 0; k < 2; ++k) c->o_part[k] = take(cur, sizeof(double) * DN_MAX_PARTIALS);
+    c->o_f = take(cur, 256);
+    if (cur > DN_STATIC_SCRATCH_BYTES) return DN_ETOOBIG;
+    c->ws_bytes = cur;
+    void* base = nullptr;
+    DN_HIP(c, static_scratch(&base));
+    c->ws = static_cast<char*>(base);
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->bound = true;
+    int rc = forward_layers(c, theta, X, dims[0], l, c->o_Zall, L);
+    if (rc != DN_OK) return rc;
+    // every partial sum this call reads is written by it first (first chunk = overwrite), nothing has to start at zero
+    return objective(c, theta, Y, l, l, true, true, nullptr, 0, ZL, f_host);
 }
 
 }  // extern "C"

@@ -107,6 +107,23 @@ def test_call_order_and_argument_errors(lib):
     lib.dn_destroy(h)
 
 
+def test_forward_static_validates_on_the_host(lib):
+    """The entry point that allocates nothing checks its arguments and the size of the problem against its fixed
+    scratch before it touches a device."""
+    fake = ctypes.c_void_p(0x1000)
+    f = ctypes.c_double()
+    dims = (ctypes.c_int * 4)(784, 300, 300, 10)
+    call = lambda L, d, C, th, l: lib.dn_forward_static(L, d, C, th, fake, fake, l, None, ctypes.byref(f), None)
+    assert call(3, dims, 1.0, fake, 20000) == -7        # 20000 rows x 612 floats > 32 MiB
+    assert call(3, dims, 0.0, fake, 20) == -1
+    assert call(3, dims, 1.0, None, 20) == -1
+    assert call(3, dims, 1.0, fake, 0) == -1
+    assert call(0, dims, 1.0, fake, 20) == -1
+    assert call(3, None, 1.0, fake, 20) == -1
+    assert lib.dn_forward_static(3, dims, 1.0, fake, fake, fake, 20, None, None, None) == -1
+    assert lib.dn_strerror(-7).decode().startswith("problem exceeds")
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N with N > 1 exits with a message before touching anything (this build is single-GPU)."""
     import subprocess
