@@ -11,7 +11,7 @@ Every array comes from numpy's counter-based Philox generator keyed by
 regenerated independently and in any order.
 
 The five configurations mirror the shapes and value ranges of the paper's
-workloads (Section 7.1 data-set table: features scaled to [0,1], one-hot
+workloads (Section 8, table of the data sets: features scaled to [0,1], one-hot
 class targets; network sizes of the same order as Table 2) without
 reproducing any data set.
 """
@@ -136,9 +136,9 @@ def make_theta(cfg: Config, bias_scale: float = 0.0, init: str = "xavier") -> np
     """Initial parameters, fp32, theta layout.
 
     init = "xavier": weights Xavier-uniform U(-a, a), a = sqrt(6 / (n_{m-1} + n_m)).
-    init = "sparse": the sparse initialisation of Section 6.2 with the count of Section 8.1: of the n_{m-1}
+    init = "sparse": the sparse initialisation of Section 6.2 with the count given among the parameters in Section 8: of the n_{m-1}
         weights into each neuron of layer m, ceil(sqrt(n_{m-1})) chosen at random are N(0, 1), the rest zero.
-    init = "dense": the dense initialisation of Section 8.3: N(0, 0.1^2) in the first layer, N(0, 0.001^2)
+    init = "dense": the dense initialisation of Section 8.2: N(0, 0.1^2) in the first layer, N(0, 0.001^2)
         in the output layer, N(0, 0.05^2) in the other layers.
     Biases: zero, or U(-bias_scale, bias_scale) when bias_scale > 0 so that
     tests exercise the bias paths.

@@ -124,6 +124,26 @@ def test_forward_static_validates_on_the_host(lib):
     assert lib.dn_strerror(-7).decode().startswith("problem exceeds")
 
 
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's host side compiled with -fsanitize=address,undefined (host code only: every -fsanitize= option
+    directly after an -Xarch_host; the device code is compiled as usual and never runs here) and driven through
+    the validation, planning and create/destroy paths by tests/abi_host_driver.cpp.  The driver checks the
+    return codes; the sanitizers abort on a bad access, on undefined behaviour and on a leak."""
+    import subprocess
+    from paper_1802_00130_amd import build
+    exe = tmp_path / "abi_host_asan"
+    cmd = [build.hipcc_path(), "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-o", str(exe), os.path.join(build.CSRC, "dn_lib.hip"), os.path.join(ROOT, "tests", "abi_host_driver.cpp")]
+    subprocess.run(cmd, check=True, capture_output=True, timeout=600)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120, env=env)
+    assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-4000:]
+    assert "host driver ok" in out.stdout
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N with N > 1 exits with a message before touching anything (this build is single-GPU)."""
     import subprocess

@@ -199,7 +199,7 @@ def test_chunked_objective_and_gradient(l_max):
 
 @pytest.mark.parametrize("init", ["sparse", "dense"])
 def test_paper_initialisations(init):
-    """Gradient and both products at the paper's own initial points (Section 6.2 sparse, Section 8.3 dense)."""
+    """Gradient and both products at the paper's own initial points (Section 6.2 sparse, Section 8.2 dense)."""
     cfg = dn_inputs.custom((200, 300, 260, 10), l=600, s=200, C=600.0, seed=17)
     w = Workload(cfg)
     w.theta = dn_inputs.make_theta(cfg, init=init)
