@@ -222,6 +222,13 @@ def run_config(args, index, steps, warmup, with_cpu_baseline, extras):
     torch.cuda.synchronize()
     prof = ctx.profile_read()
     ctx.profile_enable(False)
+    band_phases = None
+    if dominant == "jv_jtv_band":
+        # where a work-group of that kernel spends its time: one more full product with the kernel's phase clocks on
+        ctx.profile_band_phases(True)
+        dn.dn_gn_matvec(ctx, dv, out, dn.DN_FULL)
+        band_phases = ctx.profile_band_read()
+        ctx.profile_band_phases(False)
 
     # what an EMPTY event bracket reads on this stream while it is busy: the part of avg_kernel_ms that is
     # not kernel time (a profiler's per-dispatch duration does not contain it)
@@ -291,6 +298,8 @@ def run_config(args, index, steps, warmup, with_cpu_baseline, extras):
     roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
                 "frac": achieved / peak, "traffic": measured_traffic(cfg.name, dominant), "avg_kernel_ms": avg_ms,
                 "launches": int(launches), "work_per_launch": unit_work, "empty_event_bracket_ms": bracket_ms}
+    if band_phases is not None:
+        roofline["band_phase_cycles"] = band_phases
 
     mv_tflops = matvec_flops(cfg, cfg.s) / (mv_ms * 1e-3) / 1e12
     res = {

@@ -284,6 +284,18 @@ int dn_profile_num_classes(void);
 const char* dn_profile_class_name(int which);
 int dn_profile_read(dn_ctx* ctx, int which, double* total_ms_host, long long* launches_host);
 
+/*
+ * Phase clocks of the single-pass kernel for wide outputs (see dn_set_stream_passes): with on != 0 every later
+ * launch of that kernel also records, per work-group, the shader-clock cycles it spent (a) from a band's first
+ * load to the barrier behind its partial sums, (b) from there to the barrier behind the exchange with the other
+ * work-groups of its team (the wait for the slowest of them plus one round trip through memory) and (c) in the
+ * transposed product.  dn_profile_band_read synchronises the stream and returns, for the LAST such launch, the
+ * mean cycles per band of the three phases in cycles_host[0..2] and the mean number of bands per work-group in
+ * *bands_host (all zero if no such launch was made).  Costs two clock reads per phase; off by default.
+ */
+int dn_profile_band_phases(dn_ctx* ctx, int on);
+int dn_profile_band_read(dn_ctx* ctx, double* cycles_host, double* bands_host);
+
 /* HIP error code of the most recent DN_EHIP on this context (0 if none). */
 int dn_last_hip_error(const dn_ctx* ctx);
 

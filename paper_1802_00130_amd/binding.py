@@ -92,6 +92,8 @@ def load_library() -> ctypes.CDLL:
         "dn_profile_num_classes": (i, []),
         "dn_profile_class_name": (ctypes.c_char_p, [i]),
         "dn_profile_read": (i, [vp, i, P(d), P(ctypes.c_longlong)]),
+        "dn_profile_band_phases": (i, [vp, i]),
+        "dn_profile_band_read": (i, [vp, P(d), P(d)]),
         "dn_last_hip_error": (i, [vp]),
     }
     for name, (res, args) in sig.items():
@@ -107,7 +109,7 @@ EXPORTED_SYMBOLS = (
     "dn_forward_static", "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync",
     "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit",
     "dn_sync_status", "dn_profile_enable", "dn_profile_select", "dn_profile_reset", "dn_profile_num_classes",
-    "dn_profile_class_name", "dn_profile_read", "dn_last_hip_error",
+    "dn_profile_class_name", "dn_profile_read", "dn_profile_band_phases", "dn_profile_band_read", "dn_last_hip_error",
 )
 
 
@@ -202,6 +204,18 @@ class Context:
 
     def profile_reset(self) -> None:
         self._check(self._lib.dn_profile_reset(self._h), "dn_profile_reset")
+
+    def profile_band_phases(self, on: bool) -> None:
+        """Phase clocks of the single-pass kernel for wide outputs on or off."""
+        self._check(self._lib.dn_profile_band_phases(self._h, int(on)), "dn_profile_band_phases")
+
+    def profile_band_read(self) -> dict:
+        """Mean shader-clock cycles per band of the last clocked launch: loading, waiting for the exchange, rest."""
+        cyc = (ctypes.c_double * 3)()
+        bands = ctypes.c_double()
+        self._check(self._lib.dn_profile_band_read(self._h, cyc, ctypes.byref(bands)), "dn_profile_band_read")
+        return {"load_cycles": cyc[0], "exchange_wait_cycles": cyc[1], "transposed_product_cycles": cyc[2],
+                "bands_per_work_group": bands.value}
 
     def profile_read(self) -> dict:
         out = {}

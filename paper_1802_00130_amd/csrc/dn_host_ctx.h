@@ -99,7 +99,7 @@ struct dn_ctx {
     // outer Newton iteration: gradient, direction, G d, G d_prev, trial point; partial sums of 5 dot products
     size_t o_ng = 0, o_nd = 0, o_nGd = 0, o_nGdb = 0, o_ntheta = 0, o_npart = 0;
     // band kernel: exchange words, error word
-    size_t o_texch = 0, o_terr = 0;
+    size_t o_texch = 0, o_terr = 0, o_bclk = 0;
     // split structure (DN_PARTITION): per input group Q^{m,a} / T^{m,a}, per partition r, the index map that
     // lists theta partition by partition, CG vectors in that order and theta-layout operands of the product
     size_t o_Qp[DN_MAX_LAYERS + 1] = {0}, o_Tp[DN_MAX_LAYERS + 1] = {0}, o_Rp = 0, o_perm = 0, o_gperm = 0,
@@ -127,6 +127,8 @@ struct dn_ctx {
     bool band_off = false;          // a wait ran out since the last dn_bind: two-pass kernels from now on
     bool timeout_unreported = false;   // ... and dn_sync_status has not said so yet
     unsigned band_seq = 0;          // sequence numbers handed out so far
+    bool band_clocks = false;       // collect the phase clocks of the band kernel (dn_profile_band_phases)
+    int band_last_grid = 0;         // work-groups of the last band launch made with the clocks on
     int band_wgs_per_cu[3] = {0, 0, 0};   // resident work-groups per CU of each kernel variant (0: not looked up)
 
     // profiling

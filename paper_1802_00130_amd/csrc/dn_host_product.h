@@ -217,6 +217,7 @@ hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T
     ba.part = reinterpret_cast<unsigned long long*>(c->ws + c->o_texch);
     ba.error = reinterpret_cast<unsigned*>(c->ws + c->o_terr);
     ba.spin_limit = c->spin_limit;
+    ba.clk = c->band_clocks ? reinterpret_cast<unsigned long long*>(c->ws + c->o_bclk) : nullptr;
     bp.ok = true;
     return hipSuccess;
 }
@@ -236,9 +237,15 @@ hipError_t launch_band(dn_ctx* c, BandPlan& bp) {
     c->band_seq += per_launch;
     c->band_used = true;
     const dim3 grid(ba.teams * ba.ncs), block(256);
-    if (bp.GA > 1)       hipLaunchKernelGGL((jv_jtv_band_kernel<16, DN_MAX_SPLIT, 3>), grid, block, 0, c->stream, ba);
-    else if (bp.H == 16) hipLaunchKernelGGL((jv_jtv_band_kernel<16, 1, 4>), grid, block, 0, c->stream, ba);
-    else                 hipLaunchKernelGGL((jv_jtv_band_kernel<28, 1, 3>), grid, block, 0, c->stream, ba);
+    if (ba.clk) c->band_last_grid = (int)grid.x;
+    if (ba.clk) {
+        // the variants with phase clocks (a diagnostic: they need a few registers more)
+        if (bp.GA > 1)       hipLaunchKernelGGL((jv_jtv_band_kernel<16, DN_MAX_SPLIT, 3, true>), grid, block, 0, c->stream, ba);
+        else if (bp.H == 16) hipLaunchKernelGGL((jv_jtv_band_kernel<16, 1, 4, true>), grid, block, 0, c->stream, ba);
+        else                 hipLaunchKernelGGL((jv_jtv_band_kernel<28, 1, 3, true>), grid, block, 0, c->stream, ba);
+    } else if (bp.GA > 1)    hipLaunchKernelGGL((jv_jtv_band_kernel<16, DN_MAX_SPLIT, 3>), grid, block, 0, c->stream, ba);
+    else if (bp.H == 16)     hipLaunchKernelGGL((jv_jtv_band_kernel<16, 1, 4>), grid, block, 0, c->stream, ba);
+    else                     hipLaunchKernelGGL((jv_jtv_band_kernel<28, 1, 3>), grid, block, 0, c->stream, ba);
     return hipGetLastError();
 }
 

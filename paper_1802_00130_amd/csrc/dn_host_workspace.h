@@ -56,6 +56,7 @@ void layout_workspace(dn_ctx* c) {
     // band kernel: exchange words (sequence number + value)
     if (L >= 2 && c->dims[L] > 16) c->o_texch = take(cur, sizeof(unsigned long long) * kBandExchWords);
     c->o_terr = take(cur, 256);
+    c->o_bclk = take(cur, sizeof(unsigned long long) * 4 * kMaxResidentWGs);
     for (int m = 1; m <= L; ++m) {
         c->o_Qp[m] = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * c->s_max * c->ld[m]);
         c->o_Tp[m] = take(cur, sizeof(float) * (size_t)DN_MAX_SPLIT * c->s_max * c->ld[m]);

@@ -56,7 +56,14 @@ struct BandArgs {
     unsigned long long* part;            // [teams][2][ncs][GA][32]
     unsigned* error;                     // one word, nonzero after a wait ran out
     unsigned spin_limit;
+    unsigned long long* clk;             // nullable: per work-group, shader-clock cycles spent in each phase (see below)
 };
+
+// Phase clocks (diagnostic, template parameter CLK; the clocked variant needs BandArgs::clk): thread 0 of every work-group adds up the shader-clock
+// cycles between its band's first load and the barrier behind the partial sums (loading), from there to the barrier
+// behind the exchange (waiting for the slowest work-group of the team, plus the round trip through memory), and
+// from there to the end of the band (transposed product), and leaves the three sums and its band count in clk[4 b ..].
+#define DN_BAND_CLK(k) do { if (CLK && tid == 0) clk_t[k] = __builtin_readcyclecounter(); } while (0)
 
 __device__ __forceinline__ unsigned long long ll_pack(float v, unsigned seq) {
     return ((unsigned long long)seq << 32) | (unsigned long long)__builtin_bit_cast(unsigned, v);
@@ -96,7 +103,7 @@ __device__ __forceinline__ bool ll_take(const unsigned long long* base, int ga, 
 }
 
 // H rows per band, all in registers; thread (wave w, lane) owns columns j0 + 256 w + 4 lane .. + 3 of every row.
-template <int H, int GA, int WAVES_PER_SIMD>
+template <int H, int GA, int WAVES_PER_SIMD, bool CLK = false>
 __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const BandArgs ba) {
     static_assert(H <= 32, "a band's rows are exchanged in vectors of 32 words");
     __shared__ float wpart[4][GA][32];     // per-wave partial r of this slice
@@ -135,6 +142,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
     };
     const int ul = tid & 31, sub = tid >> 5;
 
+    __shared__ unsigned long long clk_sum[3], clk_t[3];
+    if (tid < 3) clk_sum[tid] = 0ull;     // (the barrier below the error check orders this before any use)
     unsigned done = 0;        // bands this team has finished
     for (int i = team; i < ba.s; i += ba.teams) {
         float4 q4[GA], tacc[GA];
@@ -150,6 +159,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
             const int u0 = rs * ba.rps;
             const int nrow = min(ba.rps, nL - u0);
             // ---- A: load the band, partial J v ------------------------------------------------
+            DN_BAND_CLK(0);
             const float* __restrict__ prow = ba.P[m] + ((long long)i * nL + u0) * ldm + j;
             float4 p[H];
 #pragma unroll
@@ -184,6 +194,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
                 }
             }
             __syncthreads();
+            DN_BAND_CLK(1);
             if (ul < H && sub < ga)
                 ll_store(&part_cur[((long long)cs * GA + sub) * 32 + ul],
                          (wpart[0][sub][ul] + wpart[1][sub][ul]) + (wpart[2][sub][ul] + wpart[3][sub][ul]), seq);
@@ -201,6 +212,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
                 for (int a = 0; a < GA; ++a) fold[sub][a][ul] = acc[a];
             }
             if (!__syncthreads_and(ok ? 1 : 0)) return;
+            DN_BAND_CLK(2);
             if (ul < H && sub < ga) {
                 const int a = sub;
                 float r = ((fold[0][a][ul] + fold[1][a][ul]) + (fold[2][a][ul] + fold[3][a][ul])) +
@@ -230,6 +242,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
                     }
                 }
             }
+            if (CLK && tid == 0) {
+                const unsigned long long c3 = __builtin_readcyclecounter();
+                clk_sum[0] += clk_t[1] - clk_t[0]; clk_sum[1] += clk_t[2] - clk_t[1]; clk_sum[2] += c3 - clk_t[2];
+            }
         }
         if (live) {
 #pragma unroll
@@ -247,6 +263,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
                 }
             }
         }
+    }
+    if (CLK && tid == 0 && ba.clk) {
+        ba.clk[blockIdx.x * 4 + 0] = clk_sum[0]; ba.clk[blockIdx.x * 4 + 1] = clk_sum[1];
+        ba.clk[blockIdx.x * 4 + 2] = clk_sum[2]; ba.clk[blockIdx.x * 4 + 3] = done;
     }
 }
 

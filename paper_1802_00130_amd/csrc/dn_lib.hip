@@ -131,6 +131,7 @@ int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     c->band_used = false;
     c->band_off = false;
     c->timeout_unreported = false;
+    c->band_last_grid = 0;
     c->split_set = false;
     // size of the chip, for kernels whose grid must be resident all at once (default kept if no device answers)
     int dev = 0, cus = 0;
@@ -689,6 +690,39 @@ int dn_profile_reset(dn_ctx* c) {
         c->prof_ms[k] = 0.0;
         c->prof_n[k] = 0;
     }
+    return DN_OK;
+}
+
+int dn_profile_band_phases(dn_ctx* c, int on) {
+    if (!c) return DN_EINVAL;
+    c->band_clocks = on != 0;
+    if (!on) c->band_last_grid = 0;
+    return DN_OK;
+}
+
+int dn_profile_band_read(dn_ctx* c, double* cycles_host, double* bands_host) {
+    if (!c || !cycles_host || !bands_host) return DN_EINVAL;
+    if (!c->bound) return DN_ESTATE;
+    cycles_host[0] = cycles_host[1] = cycles_host[2] = 0.0;
+    *bands_host = 0.0;
+    if (c->band_last_grid <= 0) return DN_OK;
+    std::vector<unsigned long long> h;
+    try {
+        h.resize((size_t)c->band_last_grid * 4);
+    } catch (const std::bad_alloc&) {
+        return DN_ENOMEM;
+    }
+    DN_HIP(c, hipMemcpyAsync(h.data(), c->ws + c->o_bclk, sizeof(unsigned long long) * h.size(), hipMemcpyDeviceToHost,
+                             c->stream));
+    DN_HIP(c, hipStreamSynchronize(c->stream));
+    double sum[3] = {0.0, 0.0, 0.0}, bands = 0.0;
+    for (int b = 0; b < c->band_last_grid; ++b) {
+        for (int k = 0; k < 3; ++k) sum[k] += (double)h[(size_t)b * 4 + k];
+        bands += (double)h[(size_t)b * 4 + 3];
+    }
+    if (bands > 0.0)
+        for (int k = 0; k < 3; ++k) cycles_host[k] = sum[k] / bands;
+    *bands_host = bands / (double)c->band_last_grid;
     return DN_OK;
 }
 

@@ -139,3 +139,23 @@ def test_wait_that_runs_out_inside_cg_still_gives_the_two_pass_iterates():
     assert it == 4 and torch.equal(d, d2)
     assert w.ctx.sync_status() == -6 and w.ctx.sync_status() == 0
     w.ctx.close()
+
+
+def test_phase_clocks_leave_the_product_unchanged():
+    """The diagnostic variant of the single-pass kernel (phase clocks on) gives the same bits and reports where a
+    work-group's cycles went; nothing is reported while the clocks are off."""
+    w = Workload(CASES["wide_layers"](), bias_scale=0.3)
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    dv, out, out2 = w.dev(dn_inputs.make_probe(w.cfg, 0)), w.empty(), w.empty()
+    dn.dn_gn_matvec(w.ctx, dv, out, dn.DN_FULL)
+    off = w.ctx.profile_band_read()
+    assert off["bands_per_work_group"] == 0 and off["load_cycles"] == 0
+    w.ctx.profile_band_phases(True)
+    dn.dn_gn_matvec(w.ctx, dv, out2, dn.DN_FULL)
+    on = w.ctx.profile_band_read()
+    w.ctx.profile_band_phases(False)
+    print(on, flush=True)
+    assert torch.equal(out, out2)
+    assert on["bands_per_work_group"] >= 1 and on["load_cycles"] > 0 and on["exchange_wait_cycles"] > 0
+    assert on["transposed_product_cycles"] > 0
+    w.ctx.close()
