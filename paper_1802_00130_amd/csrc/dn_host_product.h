@@ -154,13 +154,13 @@ hipError_t band_occupancy(dn_ctx* c, int v, int* wgs) {
     return hipSuccess;
 }
 
-// mode 0 / 1: layers 1..L-2 (block L-1 is applied as dense products around the kernel); mode 2: 1..L-1.
+// Layers 1..L-2 (block L-1 is applied as dense products around the kernel).
 // Q, T: per layer, the product's temporaries (partition mode: those of the input groups, one after another)
 hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T, BandPlan& bp) {
     bp.ok = false;
     const int L = c->L, nL = c->dims[L], s = c->s_cur;
     if (c->stream_passes == 2 || c->band_off || nL <= 16) return hipSuccess;
-    const int m_hi = mode == DN_PARTITION ? L - 1 : L - 2;
+    const int m_hi = L - 2;      // block L-1 is applied as dense products around the kernel in every mode
     if (m_hi < 1) return hipSuccess;
     BandArgs& ba = bp.ba;
     std::memset(&ba, 0, sizeof(ba));
@@ -508,6 +508,24 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
     }
     a.R = c->fptr(c->o_Rp);
     a.ldr = c->ldr;
+    // 2. the passes over the stored blocks: one pass when a sample's strips fit one work-group's registers
+    //    (as in the other modes), else the general two-pass kernels
+    {
+        // strip slots: up to 256 columns of one output group of one layer, from the multiple of four at or
+        // below the group's first column
+        int w = 0;
+        for (int m = 1; m < L; ++m)
+            for (int y = 0; y < c->split[m]; ++y)
+                for (int col = c->gbound[m][y] & ~3; col < c->gbound[m][y + 1]; col += 256, ++w)
+                    if (w < DN_MAX_WSLOTS) {
+                        a.wlayer[w] = m;
+                        a.wcol[w] = col;
+                        a.wgrp[w] = y;
+                    }
+        a.nwslots = w;
+    }
+    const bool fused = L >= 2 && c->stream_passes != 2 &&
+                       ((nL <= 16 && a.nwslots <= 16) || (nL <= 8 && a.nwslots <= DN_MAX_WSLOTS));
     // 1. inner sums over t, one product per (layer, input group); the bias term rides with group 0
     {
         GemmGroup g;
@@ -528,6 +546,12 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
                 p = mk_problem(c->fptr(c->o_ZS[m - 1]) + t0, c->ld[m - 1], v + c->woff[m] + t0, c->dims[m - 1],
                                c->fptr(c->o_Qp[m]) + (long long)x * s * c->ld[m], c->ld[m], s, c->dims[m], t1 - t0);
                 if (x == 0) p.bias = v + c->boff[m];
+                if (!fused && L >= 2 && m == L - 1) {
+                    // outside the register-strip kernel block L-1 = A^L diag(sigma') is applied as dense products: its
+                    // q leaves this product already scaled by sigma'(s^{L-1})
+                    p.aux = c->fptr(c->o_ZS[L - 1]);
+                    p.ldaux = c->ld[L - 1];
+                }
                 if (g.nprob == DN_MAX_GROUP) {
                     const int rc = flush();
                     if (rc != DN_OK) return rc;
@@ -536,24 +560,6 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         const int rc = flush();
         if (rc != DN_OK) return rc;
     }
-    // 2. the passes over the stored blocks: one pass when a sample's strips fit one work-group's registers
-    //    (as in the other modes), else the general two-pass kernels
-    {
-        // strip slots: up to 256 columns of one output group of one layer, from the multiple of four at or
-        // below the group's first column
-        int w = 0;
-        for (int m = 1; m < L; ++m)
-            for (int y = 0; y < c->split[m]; ++y)
-                for (int col = c->gbound[m][y] & ~3; col < c->gbound[m][y + 1]; col += 256, ++w)
-                    if (w < DN_MAX_WSLOTS) {
-                        a.wlayer[w] = m;
-                        a.wcol[w] = col;
-                        a.wgrp[w] = y;
-                    }
-        a.nwslots = w;
-    }
-    const bool fused = L >= 2 && c->stream_passes != 2 &&
-                       ((nL <= 16 && a.nwslots <= 16) || (nL <= 8 && a.nwslots <= DN_MAX_WSLOTS));
     if (fused) {
         ProfScope ps(c, KC_JV_JTV_FUSED);
         DN_HIP(c, ps.err);
@@ -578,10 +584,56 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
         DN_HIP(c, hipGetLastError());
         DN_HIP(c, ps.end());
     } else {
+        // Block L-1 = A^L diag(sigma') is not streamed: per partition (a, b) of layer L-1 two small dense products
+        // with the columns T_b of A^L stand in for it (q^{L-1,a} came out of step 1 scaled by sigma'):
+        //   before the passes  r^{(a,b)} = (sigma' q^{L-1,a})[:, T_b] A^L[:, T_b]^T,
+        //   after them         t^{L-1,a}[:, T_b] = sigma' * (2 r^{(a,b)} A^L[:, T_b]).
+        const long long slab = (long long)s * c->ldr;
+        auto implicit_block = [&](bool before) -> int {
+            if (L < 2) return DN_OK;
+            const int ga = c->split[L - 2], gb = c->split[L - 1];
+            GemmGroup g;
+            g.nprob = 0;
+            auto flush = [&]() -> int {
+                if (g.nprob == 0) return DN_OK;
+                ProfScope ps(c, KC_GEMM_IMPLICIT);
+                DN_HIP(c, ps.err);
+                if (before) DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_IMPLICIT>(g, 1, c->stream)));
+                else        DN_HIP(c, (launch_gemm<KC, RT, KC_GEMM_IMPLICIT>(g, 1, c->stream)));
+                DN_HIP(c, ps.end());
+                g.nprob = 0;
+                return DN_OK;
+            };
+            for (int x = 0; x < ga; ++x)
+                for (int y = 0; y < gb; ++y) {
+                    const int t0 = c->gbound[L - 1][y], t1 = c->gbound[L - 1][y + 1];
+                    float* r = c->fptr(c->o_Rp) + (long long)(c->part_base[L - 1] + x * gb + y) * slab;
+                    GemmProblem& p = g.p[g.nprob++];
+                    if (before) {
+                        p = mk_problem(c->fptr(c->o_Qp[L - 1]) + (long long)x * s * c->ld[L - 1] + t0, c->ld[L - 1],
+                                       c->fptr(c->o_AL) + t0, c->ld[L - 1], r, c->ldr, s, nL, t1 - t0);
+                    } else {
+                        p = mk_problem(r, c->ldr, c->fptr(c->o_AL) + t0, c->ld[L - 1],
+                                       c->fptr(c->o_Tp[L - 1]) + (long long)x * s * c->ld[L - 1] + t0, c->ld[L - 1], s, t1 - t0,
+                                       nL);
+                        p.aux = c->fptr(c->o_ZS[L - 1]) + t0;
+                        p.ldaux = c->ld[L - 1];
+                        p.alpha = 2.0f;
+                    }
+                    if (g.nprob == DN_MAX_GROUP) {
+                        const int rc = flush();
+                        if (rc != DN_OK) return rc;
+                    }
+                }
+            return flush();
+        };
+        int rc = implicit_block(true);
+        if (rc != DN_OK) return rc;
+        a.m_hi = L - 2;
         int chunks = 1;
-        for (int m = 1; m < L; ++m) chunks += cdiv(c->dims[m], 1024);
+        for (int m = 1; m <= a.m_hi; ++m) chunks += cdiv(c->dims[m], 1024);
         int most = 1;
-        for (int m = 1; m < L; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
+        for (int m = 1; m <= a.m_hi; ++m) most = std::max(most, c->split[m - 1] * c->split[m]);
         const size_t lds = sizeof(float) * (size_t)most * nL;
         BandPlan bp;
         {
@@ -603,7 +655,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             DN_HIP(c, hipGetLastError());
             DN_HIP(c, ps.end());
         } else {
-            if (L >= 2) {
+            if (a.m_hi >= 1) {
                 ProfScope ps(c, KC_JV);
                 DN_HIP(c, ps.err);
                 hipLaunchKernelGGL((jv_part_kernel<2>), dim3(s * cdiv(nL, 8)), dim3(256), 0, c->stream, a,
@@ -618,6 +670,8 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             DN_HIP(c, hipGetLastError());
             DN_HIP(c, ps.end());
         }
+        rc = implicit_block(false);
+        if (rc != DN_OK) return rc;
     }
     // 3. sums over samples, one product per (layer, input group) into that group's columns; bias sums apart
     TnPlan pl = plan_tn_product(c, s);

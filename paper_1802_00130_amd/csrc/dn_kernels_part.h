@@ -10,8 +10,9 @@ namespace dn {
 // from input group a to output group b (and, for a = 0, the biases of group b).  For each input group a the
 // inner sums over t in that group are Q^{m,a} (one dense product each); per partition
 //   r^{(a,b)}_i[u] = sum_{j in group b} P^m_i[u][j] q^{m,a,i}_j,     t^{m,a,i}_j = sum_u P^m_i[u][j] 2 r^{(a,b(j))}_i[u].
-// jv_part_kernel / jtv_part_kernel are the general (two-pass) form, jv_jtv_fused_part_kernel the single-pass
-// one for small outputs; all hidden layers' blocks are streamed.
+// jv_part_kernel / jtv_part_kernel are the general (two-pass) form (layers 1..L-2; block L-1 = A^L diag(sigma') is
+// applied as dense products per partition around them), jv_jtv_fused_part_kernel the single-pass one for small
+// outputs, which streams all hidden layers' blocks.
 struct PartArgs {
     int L, s, nL;
     int n[DN_MAX_LAYERS + 1];
@@ -31,6 +32,8 @@ struct PartArgs {
     int wcol[DN_MAX_WSLOTS];
     int wgrp[DN_MAX_WSLOTS];
     int ga_max, gb_max;                               // largest split[m-1] and split[m] over the hidden layers m
+    int m_hi;                                         // two-pass kernels: the stored blocks they stream are those of layers
+                                                      // 1..m_hi (L-2: block L-1 is applied as dense products around them)
 };
 
 __device__ __forceinline__ int group_of(const int* bound, int groups, int j) {
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a, const un
     int urow[RW];
 #pragma unroll
     for (int k = 0; k < RW; ++k) urow[k] = u0 + wave + 4 * k;
-    for (int m = 1; m < a.L; ++m) {
+    for (int m = 1; m <= a.m_hi; ++m) {
         const int ga = a.split[m - 1], gb = a.split[m];
         const float* __restrict__ prow[RW];
 #pragma unroll
@@ -128,11 +131,12 @@ __device__ __forceinline__ void jtv_part_block(const PartArgs& a, int chunks_tot
     const int i = vb / chunks_total;
     int c = vb - i * chunks_total;
     int m = 1;
-    for (; m < a.L; ++m) {
+    for (; m <= a.m_hi; ++m) {
         const int cm = (a.n[m] + 1023) >> 10;
         if (c < cm) break;
         c -= cm;
     }
+    if (m > a.m_hi) m = a.L;          // the chunk after the streamed layers: the output layer
     const int ga = a.split[m - 1];
     if (m == a.L) {
         // identity block: groups of outputs stay apart by themselves
