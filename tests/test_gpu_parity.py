@@ -309,9 +309,9 @@ def test_two_contexts_on_two_streams():
     calls interleaved from the host: every result matches the oracle, so nothing is shared between contexts
     and all work of a context stays on its stream."""
     cfg_a = dn_inputs.custom((30, 20, 12, 4), l=300, s=90, C=6.0, seed=71)
-    # n_L > 16 and two hidden layers: the single-pass kernel whose work-groups wait for each other runs here
-    # beside the other stream's kernels
-    cfg_b = dn_inputs.custom((18, 40, 1100, 35), l=260, s=70, C=2.0, seed=72)
+    # n_L > 16, two hidden layers, the streamed one wider than one column slice: the single-pass kernel whose
+    # work-groups (two per team here) wait for each other runs beside the other stream's kernels
+    cfg_b = dn_inputs.custom((18, 1100, 40, 35), l=260, s=70, C=2.0, seed=72)
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     work = []
     for cfg, st in zip((cfg_a, cfg_b), streams):
