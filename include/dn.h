@@ -146,6 +146,9 @@ int dn_jacobian_read(dn_ctx* ctx, int m, float* P_out);
  *   DN_FULL:       out = v/C + (1/|S|) sum_{i in S} (J^i)^T B^i J^i v,            B^i = 2I
  *   DN_BLOCKDIAG:  out_m = v_m/C + (1/|S|) sum_{i in S} (J^i_m)^T B^i J^i_m v_m   for each layer m
  * v and out must not overlap.  Needs a prior dn_jacobian_prep.
+ * The call only enqueues kernels (no allocation, no copy or memset node, no synchronisation, while profiling is
+ * off), so it may be captured in a HIP graph and replayed with new contents in v: whatever the kernels keep
+ * between launches (the sequence numbers of the single-pass kernel for wide outputs) lives in the workspace.
  */
 int dn_gn_matvec(dn_ctx* ctx, const float* v, float* out, int mode);
 

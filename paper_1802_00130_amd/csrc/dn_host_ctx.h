@@ -126,7 +126,6 @@ struct dn_ctx {
     bool band_used = false;
     bool band_off = false;          // a wait ran out since the last dn_bind: two-pass kernels from now on
     bool timeout_unreported = false;   // ... and dn_sync_status has not said so yet
-    unsigned band_seq = 0;          // sequence numbers handed out so far
     bool band_clocks = false;       // collect the phase clocks of the band kernel (dn_profile_band_phases)
     int band_last_grid = 0;         // work-groups of the last band launch made with the clocks on
     int band_wgs_per_cu[3] = {0, 0, 0};   // resident work-groups per CU of each kernel variant (0: not looked up)

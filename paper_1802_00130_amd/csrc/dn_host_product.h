@@ -178,18 +178,16 @@ hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T
         ba.Q[m] = Q[m];
         ba.T[m] = T[m];
         ba.ga[m] = mode == DN_PARTITION ? c->split[m - 1] : 1;
+        // column slices never straddle an output group (partition mode; otherwise the layer is one group); the slices of
+        // a group share their sums (per-layer and partition mode; the whole matrix: all slices, set below)
         const int groups = mode == DN_PARTITION ? c->split[m] : 1;
-        const int layer_first = ncs;
         for (int y = 0; y < groups; ++y) {
             const int glo = mode == DN_PARTITION ? c->gbound[m][y] : 0;
             const int ghi = mode == DN_PARTITION ? c->gbound[m][y + 1] : c->dims[m];
             const int first = ncs;
             for (int j0 = glo & ~3; j0 < ghi; j0 += 1024) add(m, j0, std::max(glo, j0), std::min(ghi, j0 + 1024));
-            // per-layer blocks share their sums over the whole layer (set below), partitions over the group
             for (int k = first; k < std::min(ncs, DN_MAX_BAND_SLICES); ++k) { ba.sl[k].c_lo = first; ba.sl[k].c_hi = ncs; }
         }
-        if (mode == DN_BLOCKDIAG)
-            for (int k = layer_first; k < std::min(ncs, DN_MAX_BAND_SLICES); ++k) { ba.sl[k].c_lo = layer_first; ba.sl[k].c_hi = ncs; }
     }
     if (!fits) return hipSuccess;
     if (mode == DN_FULL)
@@ -224,17 +222,17 @@ hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T
 
 hipError_t launch_band(dn_ctx* c, BandPlan& bp) {
     BandArgs& ba = bp.ba;
-    const unsigned per_launch = (unsigned)cdiv(ba.s, ba.teams) * (unsigned)ba.nrs + 1u;
-    if (!c->band_clean || c->band_seq > 0x7fff0000u) {
-        // first use after dn_bind (or the sequence numbers are about to wrap): start from a blank slate
-        hipLaunchKernelGGL(band_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ba.part, kBandExchWords, ba.error);
+    ba.per_launch = (unsigned)cdiv(ba.s, ba.teams) * (unsigned)ba.nrs + 1u;
+    ba.exch_words = kBandExchWords;
+    ba.seq = reinterpret_cast<unsigned*>(c->ws + c->o_terr) + 16;
+    if (!c->band_clean) {
+        // first use after dn_bind: exchange words, error word and sequence base start from a blank slate
+        hipLaunchKernelGGL(band_clear_kernel, dim3(1024), dim3(256), 0, c->stream, ba.part, kBandExchWords, ba.error,
+                           ba.seq);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         c->band_clean = true;
-        c->band_seq = 0;
     }
-    ba.seq_base = c->band_seq;
-    c->band_seq += per_launch;
     c->band_used = true;
     const dim3 grid(ba.teams * ba.ncs), block(256);
     if (ba.clk) c->band_last_grid = (int)grid.x;

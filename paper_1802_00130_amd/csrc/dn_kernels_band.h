@@ -24,12 +24,16 @@ namespace dn {
 // The kernel is persistent: the host sizes the grid (teams x slices) to be resident all at once, and team
 // t walks over samples t, t + teams, ...
 // Exchange between work-groups: every float travels in a 64-bit word together with a sequence number
-// (seq_base + bands done + 1, never 0), written and read with single device-scope atomic accesses.  Those
+// (base + bands done + 1, never 0), written and read with single device-scope atomic accesses.  Those
 // go through to memory, past the XCD-private L2s, so no cache write-back or invalidation is needed, and a
 // reader simply polls the word until it carries the expected number.  Two sets of words are used
 // alternately: a work-group writes set k & 1 for its k-th band after it has read all words of band k-1,
 // which exist only after every work-group of the team has finished reading band k-2, the previous user of
 // that set.
+// The base lives in device memory: every work-group reads it when it starts and the last one to finish moves it on
+// by the launch's count, so a launch that is replayed from a captured graph gets fresh numbers each time (numbers
+// baked into the launch arguments would repeat, and a word left by the previous replay could then pass for this
+// one's).  When the numbers are about to wrap that work-group also clears the exchange words.
 // Every wait is bounded: after spin_limit polls a thread raises the error word and its work-group leaves;
 // so does every work-group that sees the error word raised.  The host then runs the two-pass kernels on
 // the same product (they are enqueued behind this kernel and do nothing unless the word is raised).
@@ -52,7 +56,10 @@ struct BandArgs {
     int ga[DN_MAX_LAYERS + 1];           // input groups of layer m
     int ncs, teams, nrs, rps;            // slices, teams, bands per sample, rows per band (<= H)
     BandSlice sl[DN_MAX_BAND_SLICES];
-    unsigned seq_base;
+    unsigned* seq;                       // seq[0]: sequence numbers handed out so far (the launch's base), seq[1]: work-groups
+                                         // of this launch that have finished
+    unsigned per_launch;                 // sequence numbers this launch uses: bands per team + 1
+    long long exch_words;                // size of the exchange buffer (cleared when the numbers wrap)
     unsigned long long* part;            // [teams][2][ncs][GA][32]
     unsigned* error;                     // one word, nonzero after a wait ran out
     unsigned spin_limit;
@@ -130,6 +137,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
     if (tid == 0) flag = __hip_atomic_load(ba.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u ? 1 : 0;
     __syncthreads();
     if (!flag) return;
+    const unsigned seq_base = ba.seq[0];      // written by the previous launch's last work-group (or the clear kernel)
 
     // columns that are padding or belong to a neighbouring slice stay out of the sums
     auto mask = [&](float4& x) {
@@ -154,7 +162,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
             if (live && a < ga) q4[a] = *reinterpret_cast<const float4*>(ba.Q[m] + a * qstride + (long long)i * ldm + j);
         }
         for (int rs = 0; rs < ba.nrs; ++rs, ++done) {
-            const unsigned seq = ba.seq_base + done + 1u;
+            const unsigned seq = seq_base + done + 1u;
             unsigned long long* part_cur = part_team + (long long)(done & 1u) * ba.ncs * GA * 32;
             const int u0 = rs * ba.rps;
             const int nrow = min(ba.rps, nL - u0);
@@ -264,6 +272,20 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
             }
         }
     }
+    // the last work-group to finish moves the base on (all others have read it long ago)
+    if (tid == 0) flag = __hip_atomic_fetch_add(&ba.seq[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u ? 1 : 0;
+    __syncthreads();
+    if (flag) {
+        unsigned next = seq_base + ba.per_launch;
+        if (next > 0x7fff0000u) {
+            for (long long e = tid; e < ba.exch_words; e += 256) ba.part[e] = 0ull;
+            next = 0u;
+        }
+        if (tid == 0) {
+            ba.seq[0] = next;
+            ba.seq[1] = 0u;
+        }
+    }
     if (CLK && tid == 0 && ba.clk) {
         ba.clk[blockIdx.x * 4 + 0] = clk_sum[0]; ba.clk[blockIdx.x * 4 + 1] = clk_sum[1];
         ba.clk[blockIdx.x * 4 + 2] = clk_sum[2]; ba.clk[blockIdx.x * 4 + 3] = done;
@@ -271,10 +293,14 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
 }
 
 // exchange words to zero (sequence number 0 = nothing written) once after the workspace is bound
-__global__ void band_clear_kernel(unsigned long long* words, long long n, unsigned* error) {
+__global__ void band_clear_kernel(unsigned long long* words, long long n, unsigned* error, unsigned* seq) {
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long long)gridDim.x * blockDim.x)
         words[e] = 0ull;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *error = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *error = 0u;
+        seq[0] = 0u;
+        seq[1] = 0u;
+    }
 }
 
 }  // namespace dn

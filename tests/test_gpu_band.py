@@ -159,3 +159,54 @@ def test_phase_clocks_leave_the_product_unchanged():
     assert on["bands_per_work_group"] >= 1 and on["load_cycles"] > 0 and on["exchange_wait_cycles"] > 0
     assert on["transposed_product_cycles"] > 0
     w.ctx.close()
+
+
+@pytest.mark.parametrize("name", ["nL33_two_bands", "nL64_many_samples"])
+def test_products_replayed_from_a_captured_graph(name):
+    """Products captured in a HIP graph and replayed with new contents in the input vector: every replay must give
+    what the same call gives eagerly.  The exchange words of the single-pass kernel carry sequence numbers whose
+    base lives in device memory for exactly this (numbers fixed at capture time would repeat on every replay; with
+    at most two bands per team, as in the first case, a word left by the previous replay would then pass for the
+    current one's).  Eager products and synchronisations sit between the replays."""
+    w_cfg = CASES[name]()
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    X, theta, S = dn_inputs.make_X(w_cfg), dn_inputs.make_theta(w_cfg, bias_scale=0.3), dn_inputs.make_subset(w_cfg)
+    dev = "cuda:0"
+    dX, dth, dS = torch.from_numpy(X).to(dev), torch.from_numpy(theta).to(dev), torch.from_numpy(S).to(dev)
+    ctx = dn.Context(w_cfg.dims, w_cfg.C, 16, w_cfg.s, stream=st)
+    n = ctx.n
+    vin = torch.zeros(n, dtype=torch.float32, device=dev)
+    out_full, out_bd, eager = (torch.empty(n, dtype=torch.float32, device=dev) for _ in range(3))
+    probes = [torch.from_numpy(dn_inputs.make_probe(w_cfg, k)).to(dev) for k in range(4)]
+    with torch.cuda.stream(st):
+        dn.dn_jacobian_prep(ctx, dth, dX, dS)
+        vin.copy_(probes[0])
+        dn.dn_gn_matvec(ctx, vin, eager, dn.DN_FULL)          # first use of the kernel outside the capture
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        dn.dn_gn_matvec(ctx, vin, out_full, dn.DN_FULL)
+        dn.dn_gn_matvec(ctx, vin, out_bd, dn.DN_BLOCKDIAG)
+    for k in (1, 2, 3, 1):
+        with torch.cuda.stream(st):
+            vin.copy_(probes[k])
+            out_full.fill_(float("nan"))
+            out_bd.fill_(float("nan"))
+            g.replay()
+        st.synchronize()
+        got_full, got_bd = out_full.clone(), out_bd.clone()
+        for mode, got in ((dn.DN_FULL, got_full), (dn.DN_BLOCKDIAG, got_bd)):
+            with torch.cuda.stream(st):
+                dn.dn_gn_matvec(ctx, probes[k], eager, mode)
+            assert ctx.sync_status() == 0
+            assert torch.equal(got, eager), (name, k, mode)
+    # against the oracle once, so that "equal" is also "right"
+    ref = orc_matvec(w_cfg, theta, X[S], dn_inputs.make_probe(w_cfg, 1))
+    assert rel_l2(got_full.cpu().numpy(), ref) <= TOL
+    ctx.close()
+
+
+def orc_matvec(cfg, theta, XS, v):
+    from oracle import dn_oracle as orc
+    return orc.gn_matvec(theta.astype(np.float64), cfg.dims, cfg.C, XS.astype(np.float64), v.astype(np.float64))
