@@ -99,11 +99,13 @@ int dn_forward(dn_ctx* ctx, const float* theta, const float* X, const float* Y, 
                double* f_host, float* ZL);
 
 /*
- * dn_forward for callers that cannot allocate device memory or keep a workspace: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Same value f (and outputs ZL, nullable) as
- * dn_forward on a context with l_max >= l, but no context and no workspace: the activations and partial sums
- * live in a scratch array that is part of the library's device code (DN_STATIC_SCRATCH_BYTES per GPU, held from
- * the first call on that GPU until the process ends).  The call allocates nothing, on the host or on the device.
+ * dn_forward for callers that cannot allocate device memory or keep a workspace: tight serving loops, harnesses
+ * that forbid hipMalloc, processes that may not grow their memory once they run.  Same value f (and outputs ZL,
+ * nullable) as dn_forward on a context with l_max >= l, but no context and no workspace: the activations and
+ * partial sums live in a scratch array that is part of the library's device code (DN_STATIC_SCRATCH_BYTES per GPU,
+ * held from the first call on that GPU until the process ends).  The call allocates nothing, on the host or on
+ * the device.  (It returns f on the host and therefore synchronises the stream: it cannot itself be recorded
+ * into a graph.)
  * dims[0..L], C as in dn_create; theta, X, Y, ZL are device pointers as in dn_forward; the work is enqueued on
  * hip_stream (hipStream_t as void*, NULL = default stream), which is synchronised before *f_host is written.
  * The scratch needed is 4 l sum_{m=1..L} roundup4(n_m) bytes plus 17 KB; a problem beyond the limit is rejected
