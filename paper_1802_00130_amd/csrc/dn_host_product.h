@@ -415,7 +415,8 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
             DN_HIP(c, ps.end());
         }
     }
-    // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1]
+    // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1] (the right operand transposed once by
+    //    dn_jacobian_prep: K-contiguous, the ones as a real row)
     TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
@@ -423,15 +424,14 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
         g.nprob = L;
         for (int m = 1; m <= L; ++m) {
             GemmProblem& p = g.p[m - 1];
-            p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]), c->ld[m - 1],
+            p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZST[m - 1]), c->ld_s,
                            c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
-            p.b_ones_col = 1;
             p.split_stride = tn_slice_floats(c, m);
             p.c_rows_padded = 1;
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     // 4. fold slices, scale by 1/|S|, add v/C
@@ -681,7 +681,7 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             if (g.nprob == 0) return DN_OK;
             ProfScope ps(c, KC_GEMM_TN_MATVEC);
             DN_HIP(c, ps.err);
-            DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
+            DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
             DN_HIP(c, ps.end());
             g.nprob = 0;
             return DN_OK;
@@ -690,8 +690,9 @@ int gn_matvec_part(dn_ctx* c, const float* v, float* out) {
             for (int x = 0; x < c->split[m - 1]; ++x) {
                 const int t0 = c->gbound[m - 1][x], t1 = c->gbound[m - 1][x + 1];
                 GemmProblem& p = g.p[g.nprob++];
-                p = mk_problem(c->fptr(c->o_Tp[m]) + (long long)x * s * c->ld[m], c->ld[m], c->fptr(c->o_ZS[m - 1]) + t0,
-                               c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m] + t0, c->ldw[m], c->dims[m], t1 - t0, s);
+                p = mk_problem(c->fptr(c->o_Tp[m]) + (long long)x * s * c->ld[m], c->ld[m],
+                               c->fptr(c->o_ZST[m - 1]) + (long long)t0 * c->ld_s, c->ld_s,
+                               c->fptr(c->o_tn) + pl.offset[m] + t0, c->ldw[m], c->dims[m], t1 - t0, s);
                 p.split_stride = tn_slice_floats(c, m);
                 if (g.nprob == DN_MAX_GROUP) {
                     const int rc = flush();

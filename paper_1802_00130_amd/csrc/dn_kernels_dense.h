@@ -88,6 +88,32 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict_
     }
 }
 
+// dst[c][r] = src[r][c] for c < cols, and one more row dst[cols][r] = 1: the activations of the subsample with the
+// sample index contiguous and the constant input of the bias terms as a last row (Section 4.2: the outer sums over
+// samples then read this operand K-contiguously; it is the same for every product until the next dn_jacobian_prep).
+__global__ __launch_bounds__(256) void transpose_ones_kernel(const float* __restrict__ src, long long lds_src,
+                                                             float* __restrict__ dst, long long ld_dst, int rows,
+                                                             int cols) {
+    __shared__ float tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) {
+        const int rr = by + ty + k, cc = bx + tx;
+        if (rr < rows && cc < cols) tile[ty + k][tx] = src[(long long)rr * lds_src + cc];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) {
+        const int cc = bx + ty + k, rr = by + tx;
+        if (rr < rows && cc < cols) dst[(long long)cc * ld_dst + rr] = tile[tx][ty + k];
+    }
+    if (blockIdx.x == 0) {
+        const int rr = by + (threadIdx.x & 31);
+        if (threadIdx.x < 32 && rr < rows) dst[(long long)cols * ld_dst + rr] = 1.0f;
+    }
+}
+
 // Dense copy of a stored block (drops the row padding).
 __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                          long long rows, int cols, long long ld) {

@@ -304,6 +304,17 @@ int dn_jacobian_prep(dn_ctx* c, const float* theta, const float* X, int l, const
     // z^{m,i} for the hidden layers (the output layer's activations are not needed by the products)
     int rc = forward_layers(c, theta, c->fptr(c->o_ZS[0]), c->ld[0], s, c->o_ZS, L - 1);
     if (rc != DN_OK) return rc;
+    {
+        // [Z^m_S, 1]^T for the sums over samples of every later product (their right operand, K-contiguous)
+        ProfScope ps(c, KC_GATHER);
+        DN_HIP(c, ps.err);
+        for (int m = 0; m < L; ++m) {
+            hipLaunchKernelGGL(transpose_ones_kernel, dim3(cdiv(c->dims[m], 32), cdiv(s, 32)), dim3(256), 0, c->stream,
+                               c->fptr(c->o_ZS[m]), c->ld[m], c->fptr(c->o_ZST[m]), c->ld_s, s, c->dims[m]);
+            DN_HIP(c, hipGetLastError());
+        }
+        DN_HIP(c, ps.end());
+    }
     if (L >= 2) {
         ProfScope ps(c, KC_JAC_INIT);
         DN_HIP(c, ps.err);
@@ -655,15 +666,14 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
         g.nprob = L;
         for (int m = 1; m <= L; ++m) {
             GemmProblem& p = g.p[m - 1];
-            p = mk_problem(m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZS[m - 1]),
-                           c->ld[m - 1], c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
-            p.b_ones_col = 1;
+            p = mk_problem(m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZST[m - 1]),
+                           c->ld_s, c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
             p.split_stride = tn_slice_floats(c, m);
             p.c_rows_padded = 1;
         }
         ProfScope ps(c, KC_GEMM_TN_MATVEC);
         DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, RT, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
+        DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
         DN_HIP(c, ps.end());
     }
     return tn_reduce(c, &pl, false, v, out, 2.0 / (double)s);
