@@ -150,7 +150,7 @@ int dn_jacobian_read(dn_ctx* ctx, int m, float* P_out);
  * v and out must not overlap.  Needs a prior dn_jacobian_prep.
  * The call only enqueues kernels (no allocation, no copy or memset node, no synchronisation, while profiling is
  * off), so it may be captured in a HIP graph and replayed with new contents in v: whatever the kernels keep
- * between launches (the sequence numbers of the single-pass kernel for wide outputs) lives in the workspace.
+ * between launches (the sequence numbers of the single-pass kernel in which work-groups share a sample) lives in the workspace.
  */
 int dn_gn_matvec(dn_ctx* ctx, const float* v, float* out, int mode);
 
@@ -258,8 +258,9 @@ int dn_set_split(dn_ctx* ctx, const int* groups);
 int dn_num_partitions(const dn_ctx* ctx);
 
 /*
- * Products with n_L > 16 read each stored block ONCE per product by letting a team of work-groups share a
- * sample (the kernel's work-groups exchange partial sums through device memory and wait for each other;
+ * Products whose stored blocks do not fit one work-group's registers (n_L > 16, or hidden layers wider than 8192
+ * in total; at least two hidden layers) read each stored block ONCE per product by letting a team of work-groups
+ * share a sample (the kernel's work-groups exchange partial sums through device memory and wait for each other;
  * every wait is bounded).  dn_set_stream_passes(ctx, 2) selects the plain two-pass kernels instead (one read
  * for J v, one for J^T), 0 restores the automatic choice.
  * dn_set_spin_limit sets the number of polls after which such a wait gives up (default 1 << 20, a few
@@ -290,7 +291,7 @@ const char* dn_profile_class_name(int which);
 int dn_profile_read(dn_ctx* ctx, int which, double* total_ms_host, long long* launches_host);
 
 /*
- * Phase clocks of the single-pass kernel for wide outputs (see dn_set_stream_passes): with on != 0 every later
+ * Phase clocks of the single-pass kernel in which work-groups share a sample (see dn_set_stream_passes): with on != 0 every later
  * launch of that kernel also records, per work-group, the shader-clock cycles it spent (a) from a band's first
  * load to the barrier behind its partial sums, (b) from there to the barrier behind the exchange with the other
  * work-groups of its team (the wait for the slowest of them plus one round trip through memory) and (c) in the

@@ -121,7 +121,7 @@ struct dn_ctx {
     int s_cur = 0;
     int last_hip = 0;
     int num_cus = 256;
-    // band kernel (single pass over the stored blocks for n_L > 16)
+    // band kernel (single pass over the stored blocks where the register-strip kernel does not fit)
     int stream_passes = 0;          // 0 automatic, 2 force the two-pass kernels
     unsigned spin_limit = 1u << 20;
     bool band_clean = false;        // exchange words and error word cleared since the last dn_bind

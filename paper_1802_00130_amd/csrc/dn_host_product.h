@@ -129,7 +129,7 @@ void fill_stream_args(const dn_ctx* c, StreamArgs& a, int mode) {
     a.nwslots = w;
 }
 
-// ---- single pass over the stored blocks for wide outputs: plumbing of jv_jtv_band_kernel ----------------
+// ---- single pass over the stored blocks by teams of work-groups: plumbing of jv_jtv_band_kernel ---------
 // grid of the two-pass kernels when they are enqueued as the fall-back of the band kernel: they walk over their
 // virtual work-groups, and a launch that finds nothing to do should cost next to nothing
 constexpr int kFallbackGrid = 2048;
@@ -159,7 +159,7 @@ hipError_t band_occupancy(dn_ctx* c, int v, int* wgs) {
 hipError_t plan_band(dn_ctx* c, int mode, const float* const* Q, float* const* T, BandPlan& bp) {
     bp.ok = false;
     const int L = c->L, nL = c->dims[L], s = c->s_cur;
-    if (c->stream_passes == 2 || c->band_off || nL <= 16) return hipSuccess;
+    if (c->stream_passes == 2 || c->band_off) return hipSuccess;
     const int m_hi = L - 2;      // block L-1 is applied as dense products around the kernel in every mode
     if (m_hi < 1) return hipSuccess;
     BandArgs& ba = bp.ba;

@@ -56,7 +56,7 @@ void layout_workspace(dn_ctx* c) {
     c->o_ntheta = take(cur, nvec);
     c->o_npart = take(cur, sizeof(double) * 5 * DN_MAX_PARTIALS);
     // band kernel: exchange words (sequence number + value)
-    if (L >= 2 && c->dims[L] > 16) c->o_texch = take(cur, sizeof(unsigned long long) * kBandExchWords);
+    if (L >= 3) c->o_texch = take(cur, sizeof(unsigned long long) * kBandExchWords);
     c->o_terr = take(cur, 256);
     c->o_bclk = take(cur, sizeof(unsigned long long) * 4 * kMaxResidentWGs);
     for (int m = 1; m <= L; ++m) {

@@ -1,4 +1,5 @@
-// Single pass over the stored blocks for wide outputs (n_L > 16): teams of work-groups sharing a sample.
+// Single pass over the stored blocks by teams of work-groups sharing a sample (wide outputs, n_L > 16, and narrow
+// ones whose hidden layers exceed the register-strip kernel).
 #pragma once
 #include "dn_common.h"
 #include "dn_kernels_stream.h"

@@ -1,5 +1,6 @@
-"""GPU parity of the single-pass product kernel for wide outputs (teams of work-groups share a sample), n_L > 16
-with at least two hidden layers.
+"""GPU parity of the single-pass product kernel in which teams of work-groups share a sample: every product
+with at least two hidden layers that the register-strip kernel cannot take (n_L > 16, or hidden layers too wide
+for one work-group's registers).
 
 Each case runs the product with that kernel (automatic choice) and with the two-pass kernels forced, both
 against the fp64 oracle (1e-4 relative L2), in full and per-layer mode.  Output widths are chosen to hit both
@@ -31,6 +32,10 @@ CASES = {
     "nL1000": lambda: dn_inputs.custom((16, 70, 33, 20, 1000), l=60, s=20, C=5.0, seed=65),
     "wide_layers": lambda: dn_inputs.custom((12, 2100, 1030, 25, 40), l=80, s=37, C=5.0, seed=66),
     "nL33_two_bands": lambda: dn_inputs.custom((9, 1025, 77, 14, 33), l=150, s=90, C=3.0, seed=67),
+    # narrow outputs whose hidden layers exceed the register-strip kernel (more than 32 strips; n_L = 16 with more than 16)
+    "nL10_wide_hidden": lambda: dn_inputs.custom((12, 4300, 4100, 30, 10), l=40, s=14, C=5.0, seed=68),
+    "nL16_wide_hidden": lambda: dn_inputs.custom((8, 2200, 2100, 16), l=70, s=33, C=5.0, seed=69),
+    "nL3_deep_wide": lambda: dn_inputs.custom((6, 3000, 3100, 2300, 3), l=30, s=12, C=2.0, seed=70),
 }
 
 
@@ -61,8 +66,9 @@ def test_single_pass_and_two_pass_products_match_the_oracle(name):
     w.ctx.close()
 
 
-def test_single_pass_kernel_is_the_one_that_runs():
-    w = Workload(CASES["nL100"](), bias_scale=0.3)
+@pytest.mark.parametrize("name", ["nL100", "nL16_wide_hidden"])
+def test_single_pass_kernel_is_the_one_that_runs(name):
+    w = Workload(CASES[name](), bias_scale=0.3)
     dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
     dv, out = w.dev(dn_inputs.make_probe(w.cfg, 0)), w.empty()
     w.ctx.profile_enable(True)

@@ -31,6 +31,8 @@ CASES = {
     # are no multiples of four, several bands of rows per sample
     "wide_out_2-3-4-1": (lambda: dn_inputs.custom((14, 2600, 1701, 37), l=40, s=10, C=4.0, seed=80), (2, 3, 4, 1)),
     "wide_out_3-2-3-4": (lambda: dn_inputs.custom((20, 1030, 45, 130), l=300, s=260, C=4.0, seed=81), (3, 2, 3, 4)),
+    # narrow outputs, hidden layers beyond the register-strip kernel: the same single-pass kernel
+    "narrow_out_wide_hidden_2-2-3-1": (lambda: dn_inputs.custom((9, 2300, 2200, 16), l=50, s=21, C=4.0, seed=83), (2, 2, 3, 1)),
     "wide_out_deep": (lambda: dn_inputs.custom((33, 2100, 530, 1200, 100), l=60, s=24, C=9.0, seed=82), (1, 2, 2, 2, 1)),
 }
 
