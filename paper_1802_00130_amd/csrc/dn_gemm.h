@@ -313,8 +313,11 @@ __device__ __forceinline__ void frag_read(const float* lds, int row, int kk, int
 // PIN = use the hand-interleaved steady-state loop.
 // CLS = caller's kernel-class number; it changes no code, only the symbol, so that a profiler's
 //       per-kernel statistics separate the call sites (forward, back-propagation, sweeps, products...).
+// Tiles of 128 x 128 are compiled for two work-groups per CU (at most 256 registers): alone on a CU a work-group's
+// epilogue (sigmoid, or the sigma' scaling with its extra loads) leaves the matrix pipes idle, which costs up to 9 % of
+// the launch (2000000 x 4096 x 4096 with the sigma' scaling: 518 ms with one work-group per CU, 476 ms with two).
 template <int BM, int BN, int BK, int WGM, int WGN, int LA, int LB, int PF, bool PIN, int CLS>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmGroup g) {
+__global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 1)) void gemm_kernel(const GemmGroup g) {
     constexpr int NT = 256;
     static_assert(WGM * WGN == 4, "four waves per work-group");
     constexpr int WM = BM / WGM, WN = BN / WGN;

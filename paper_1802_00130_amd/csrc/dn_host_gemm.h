@@ -74,9 +74,28 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
 // 64x64 tiles, K-tile 16, 4 K-tiles in flight (2 for short sums and for sums over samples).  The hand-placed
 // schedule is used for launches of at most 4 work-groups per CU and, at every size, when both operands go through
 // the transposing loads (sums over samples); elsewhere the compiler's schedule of the plain loop is as good.
-// 128x128 tiles (one work-group per CU) were dropped: with the XCD-aware tile walk, 64x64 tiles are as fast or
-// faster at every shape of the path (2048-2000-2000-2000-100: Jacobian sweeps 82.1 -> 71.5 ms, gradient
-// 69.0 -> 61.3 ms; 4096 x 5 - 1000: sweeps 1779 -> 1671 ms, gradient 714 -> 670 ms).
+// 128x128 tiles (64x64 per wave: half the LDS and L2 traffic per flop; two work-groups per CU, hand-placed schedule)
+// pay when the launch fills whole rounds of work-groups and loses little to padding: measured stand-alone against
+// the 64x64 tiles with K-tiles of 32, 200000 x 4096 x 4096 132 -> 142 TFLOP/s (130 -> 141 with the sigma' scaling),
+// 100000 x 2000 x 2000 with bias and sigmoid 119 -> 133, 2000 x 4096 x 4096 (512 tiles) 126 -> 137, but 5000 x 2000 x 2048
+// (640 tiles: two and a half rounds of 256) 124 -> 110.  In the step (4096 x 5 - 1000): forward 219 -> 204 ms, gradient
+// 627 -> 600 ms, Jacobian sweeps 1548 -> 1437 ms; 2048-2000-2000-2000-100: 21.1 -> 19.1, 63.9 -> 56.6, 73.5 -> 63.3 ms.
+bool prefer_128(const GemmGroup& g) {
+    double steps128 = 0.0, steps64 = 0.0;      // in K-tile steps of a 64x64 tile
+    long long t128 = 0;
+    for (int i = 0; i < g.nprob; ++i) {
+        const GemmProblem& p = g.p[i];
+        const long long a = (long long)cdiv(p.M, 128) * cdiv(p.N, 128), b = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
+        t128 += a;
+        steps128 += 4.0 * (double)a * cdiv(p.K, 16);
+        steps64 += (double)b * cdiv(p.K, 16);
+    }
+    if (t128 < 2 * 256) return false;
+    const double rounds = (double)cdiv(t128, 256);
+    const double fill = (double)t128 / (256.0 * rounds);
+    return steps128 / (fill * 1.08) < 0.97 * steps64;
+}
+
 template <int LA, int LB, int CLS>
 hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
     finalize_group(g, 64, 64, 16, splits);
@@ -87,6 +106,10 @@ hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
     // through the transposing loads leaves room for a fourth work-group per CU and is 3-9 % faster at every shape
     // (4096 x 4097 x 2000: 595 -> 565 us, 1000 x 3073 x 2500: 187 -> 171 us, 300 x 785 x 3000 in 8 slices 26.7 -> 25.6 us)
     if (LA == RT && LB == KC) return launch_gemm_t<64, 64, 16, 2, LA, LB, CLS, true>(g, st);
+    if (LA == KC && LB == KC && splits == 1 && prefer_128(g)) {
+        finalize_group(g, 128, 128, 16, splits);
+        return launch_gemm_t<128, 128, 16, 2, LA, LB, CLS, true>(g, st);
+    }
     if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
     // short sums (K <= 1024): two K-tiles in flight are enough, and the smaller register footprint lets a fifth
     // work-group onto each CU (60000 x 300 x 300: 119 -> 113 us)

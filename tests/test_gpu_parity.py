@@ -12,7 +12,7 @@ import torch
 import dn_inputs
 import paper_1802_00130_amd as dn
 from oracle import dn_oracle as orc
-from tests.gpu_common import Workload, rel_l2
+from tests.gpu_common import Workload, assert_close_blocks, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -276,11 +276,12 @@ WIDE = {
     # n_L <= 12, hidden widths 4096 < total <= 8192: the fused kernel with two strips per wave
     "fused2_16-2500-2100-10": lambda: dn_inputs.custom((16, 2500, 2100, 10), l=40, s=12, C=4.0, seed=81),
     "fused2_12-4100-3": lambda: dn_inputs.custom((12, 4100, 3), l=30, s=9, C=2.0, seed=82),
-    # n_L <= 16 but too wide for the fused kernel: the two-pass kernels with a small output layer
-    "twopass_small_nL_8-5000-4000-6": lambda: dn_inputs.custom((8, 5000, 4000, 6), l=30, s=8, C=3.0, seed=83),
+    # n_L <= 16 but too wide for the fused kernel: teams of work-groups share a sample (two hidden layers or more) ...
+    "band_small_nL_8-5000-4000-6": lambda: dn_inputs.custom((8, 5000, 4000, 6), l=30, s=8, C=3.0, seed=83),
+    # ... and with one hidden layer nothing is streamed at all (block L-1 is applied as dense products)
     "twopass_small_nL_10-8500-5": lambda: dn_inputs.custom((10, 8500, 5), l=30, s=8, C=3.0, seed=84),
-    # 12 < n_L <= 16 with more than 4096 hidden columns: no fused variant, two-pass
-    "twopass_nL14_9-3000-1500-14": lambda: dn_inputs.custom((9, 3000, 1500, 14), l=30, s=8, C=3.0, seed=85),
+    # 12 < n_L <= 16 with more than 4096 hidden columns: no fused variant
+    "band_nL14_9-3000-1500-14": lambda: dn_inputs.custom((9, 3000, 1500, 14), l=30, s=8, C=3.0, seed=85),
 }
 
 
@@ -301,6 +302,36 @@ def test_wide_hidden_layers_small_output(name):
     prof = w.ctx.profile_read()
     assert (prof["jv_jtv_fused"][1] == 2) == name.startswith("fused2")
     assert (prof["jv_rows"][1] == 2) == name.startswith("twopass")
+    assert (prof["jv_jtv_band"][1] == 2) == name.startswith("band")
+    w.ctx.close()
+
+
+def test_large_tiles_with_ragged_edges():
+    """Launches big enough for the 128 x 128 tiles of the GEMM engine (whole rounds of two work-groups per CU), with
+    ragged edges in every dimension: 32700 rows (255.5 tiles), 1150 columns (8.98 tiles), sums over 270 and 530 terms
+    (neither a multiple of the K-tile), the bias + sigmoid epilogue (forward), the sigma' epilogue (back-propagation)
+    and the sigma' epilogue with one activation row per n_L output rows (the sweeps over the stored blocks,
+    818 * 40 = 32720 rows)."""
+    cfg = dn_inputs.custom((270, 1150, 530, 40), l=32700, s=818, C=100.0, seed=86)
+    w = Workload(cfg, bias_scale=0.3)
+    th, X64, Y64 = w.theta.astype(np.float64), w.X.astype(np.float64), w.Y.astype(np.float64)
+    ZL = torch.empty(w.l, cfg.dims[-1], dtype=torch.float32, device="cuda:0")
+    f = dn.dn_forward(w.ctx, w.dtheta, w.dX, w.dY, ZL)
+    g = w.empty()
+    f2 = dn.dn_grad(w.ctx, w.dtheta, w.dX, w.dY, g)
+    g_ref, f_ref = orc.grad(th, cfg.dims, cfg.C, X64, Y64)
+    assert abs(f - f_ref) <= TOL * abs(f_ref) and abs(f2 - f_ref) <= TOL * abs(f_ref)
+    assert rel_l2(ZL.cpu().numpy(), orc.forward(th, cfg.dims, X64)[-1]) <= TOL
+    whole, worst = assert_close_blocks(g.cpu().numpy(), g_ref, cfg.dims, TOL, "gradient")
+    print(f"  gradient: rel err {whole:.2e}, worst block {worst}", flush=True)
+    dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, w.dS)
+    P_ref = orc.jacobian_blocks(th, cfg.dims, w.XS64)
+    for m in range(1, cfg.L):
+        P = torch.empty(w.s, cfg.dims[-1], cfg.dims[m], dtype=torch.float32, device="cuda:0")
+        dn.dn_jacobian_read(w.ctx, m, P)
+        err = rel_l2(P.cpu().numpy(), P_ref[m - 1])
+        print(f"  P^{m}: rel err {err:.2e}", flush=True)
+        assert err <= TOL, f"P^{m}"
     w.ctx.close()
 
 
