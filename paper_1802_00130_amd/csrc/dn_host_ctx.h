@@ -90,6 +90,7 @@ struct dn_ctx {
     size_t o_ZS[DN_MAX_LAYERS + 1] = {0};
     size_t o_ZST[DN_MAX_LAYERS + 1] = {0};   // [Z^m_S, 1]^T: (n_m + 1) rows of ld_s floats, m = 0..L-1
     long long ld_s = 0;                      // row stride of those: s_max rounded up to 4
+    size_t o_TT[DN_MAX_LAYERS + 1] = {0};    // (T^m)^T: n_m rows of ld_s floats, m = 1..L (large products only)
     size_t o_P[DN_MAX_LAYERS + 1] = {0};
     size_t o_Q[DN_MAX_LAYERS + 1] = {0};
     size_t o_Qb = 0;           // second half of one layer's Q when its sum over t is cut in two

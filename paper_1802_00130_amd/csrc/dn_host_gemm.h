@@ -80,10 +80,12 @@ hipError_t launch_gemm_t(const GemmGroup& g, hipStream_t st) {
 // 100000 x 2000 x 2000 with bias and sigmoid 119 -> 133, 2000 x 4096 x 4096 (512 tiles) 126 -> 137, but 5000 x 2000 x 2048
 // (640 tiles: two and a half rounds of 256) 124 -> 110.  In the step (4096 x 5 - 1000): forward 219 -> 204 ms, gradient
 // 627 -> 600 ms, Jacobian sweeps 1548 -> 1437 ms; 2048-2000-2000-2000-100: 21.1 -> 19.1, 63.9 -> 56.6, 73.5 -> 63.3 ms.
-bool prefer_128(const GemmGroup& g) {
+// `only`: bit i set = problem i takes part (all by default).
+bool prefer_128(const GemmGroup& g, unsigned only = ~0u) {
     double steps128 = 0.0, steps64 = 0.0;      // in K-tile steps of a 64x64 tile
     long long t128 = 0;
     for (int i = 0; i < g.nprob; ++i) {
+        if (!((only >> i) & 1u)) continue;
         const GemmProblem& p = g.p[i];
         const long long a = (long long)cdiv(p.M, 128) * cdiv(p.N, 128), b = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
         t128 += a;
@@ -96,20 +98,47 @@ bool prefer_128(const GemmGroup& g) {
     return steps128 / (fill * 1.08) < 0.97 * steps64;
 }
 
+// Which problems of a group go through the large tiles: all of them if the whole group passes the test above;
+// else the problems with at least a round of large tiles each, if they pass it among themselves (the rest then
+// gets a launch of small tiles of its own: the inner sums of 4096 x 5 - 1000 over 2000 samples are four layers of 512
+// large tiles, exactly four rounds, and a fifth of 128, which as small tiles costs 0.13 ms instead of a fifth round:
+// 2.43 -> 2.1 ms); else none.
+unsigned pick_128(const GemmGroup& g) {
+    const unsigned all = g.nprob >= 32 ? ~0u : ((1u << g.nprob) - 1u);
+    if (prefer_128(g, all)) return all;
+    unsigned big = 0;
+    for (int i = 0; i < g.nprob; ++i)
+        if ((long long)cdiv(g.p[i].M, 128) * cdiv(g.p[i].N, 128) >= 256) big |= 1u << i;
+    if (big != 0 && big != all && prefer_128(g, big)) return big;
+    return 0;
+}
+
 template <int LA, int LB, int CLS>
 hipError_t launch_gemm(GemmGroup& g, int splits, hipStream_t st) {
-    finalize_group(g, 64, 64, 16, splits);
     // sums over samples (both operands through the transposing loads): two K-tiles in flight (measured 4-6 % faster
     // than four at every shape: 300 x 785 x 3000 in 8 slices 30.0 -> 28.2 us, 1024 x 1024 x 60000 1157 -> 1097 us)
+    if (LA == RT || LB == RT) finalize_group(g, 64, 64, 16, splits);
     if (LA == RT && LB == RT) return launch_gemm_t<64, 64, 16, 2, LA, LB, CLS, true>(g, st);
     // sums over samples whose right operand was transposed beforehand (the products): the same schedule; one operand
     // through the transposing loads leaves room for a fourth work-group per CU and is 3-9 % faster at every shape
     // (4096 x 4097 x 2000: 595 -> 565 us, 1000 x 3073 x 2500: 187 -> 171 us, 300 x 785 x 3000 in 8 slices 26.7 -> 25.6 us)
     if (LA == RT && LB == KC) return launch_gemm_t<64, 64, 16, 2, LA, LB, CLS, true>(g, st);
-    if (LA == KC && LB == KC && splits == 1 && prefer_128(g)) {
-        finalize_group(g, 128, 128, 16, splits);
-        return launch_gemm_t<128, 128, 16, 2, LA, LB, CLS, true>(g, st);
+    if (LA == KC && LB == KC && splits == 1) {
+        const unsigned large = pick_128(g);
+        if (large != 0) {
+            GemmGroup a, b;
+            a.nprob = b.nprob = 0;
+            for (int i = 0; i < g.nprob; ++i) {
+                if ((large >> i) & 1u) a.p[a.nprob++] = g.p[i];
+                else                   b.p[b.nprob++] = g.p[i];
+            }
+            finalize_group(a, 128, 128, 16, splits);
+            const hipError_t e = launch_gemm_t<128, 128, 16, 2, LA, LB, CLS, true>(a, st);
+            if (e != hipSuccess || b.nprob == 0) return e;
+            g = b;      // the rest: small tiles, chosen below
+        }
     }
+    finalize_group(g, 64, 64, 16, splits);
     if (g.total_tiles <= 4 * 256) return launch_gemm_t<64, 64, 16, 4, LA, LB, CLS, true>(g, st);
     // short sums (K <= 1024): two K-tiles in flight are enough, and the smaller register footprint lets a fifth
     // work-group onto each CU (60000 x 300 x 300: 119 -> 113 us)

@@ -263,6 +263,63 @@ int band_status(dn_ctx* c) {
 
 int gn_matvec_part(dn_ctx* c, const float* v, float* out);
 
+// Sums over samples of a product, all layers in one launch: W_m = left_m^T [Z^{m-1}, 1] into the partial-sum buffer
+// (left_m = T^m: s rows of ld[m] floats).  The right operand was transposed once by dn_jacobian_prep (K-contiguous,
+// the ones of the bias terms as a real row).  The left one is new in every product and normally goes through the
+// transposing loads of the tile engine; when the launch is large enough for the 128 x 128 tiles, it is transposed
+// first (one pass over s x sum n_m floats) and both operands are read K-contiguously: 4096 x 5 - 1000, 2000 samples,
+// 2.57 -> 2.2 ms including the copy.
+int sums_over_samples(dn_ctx* c, int s, const float* const* left, const TnPlan& pl) {
+    const int L = c->L;
+    GemmGroup g;
+    g.nprob = L;
+    if (pl.splits == 1) {
+        for (int m = 1; m <= L; ++m) {
+            GemmProblem& p = g.p[m - 1];
+            p = mk_problem(c->fptr(c->o_TT[m]), c->ld_s, c->fptr(c->o_ZST[m - 1]), c->ld_s,
+                           c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
+            p.split_stride = tn_slice_floats(c, m);
+        }
+        if (pick_128(g) != 0) {
+            TransposeArgs ta;
+            std::memset(&ta, 0, sizeof(ta));
+            ta.nprob = L;
+            ta.rows = s;
+            ta.tiles_r = cdiv(s, 64);
+            ta.ld_dst = c->ld_s;
+            int blocks = 0;
+            for (int m = 1; m <= L; ++m) {
+                ta.src[m - 1] = left[m];
+                ta.dst[m - 1] = c->fptr(c->o_TT[m]);
+                ta.ld_src[m - 1] = c->ld[m];
+                ta.cols[m - 1] = c->dims[m];
+                ta.first[m - 1] = blocks;
+                blocks += ta.tiles_r * cdiv(c->dims[m], 64);
+            }
+            ta.first[L] = blocks;
+            ProfScope ps(c, KC_GEMM_TN_MATVEC);
+            DN_HIP(c, ps.err);
+            hipLaunchKernelGGL(transpose_group_kernel, dim3(blocks), dim3(256), 0, c->stream, ta);
+            DN_HIP(c, hipGetLastError());
+            DN_HIP(c, (launch_gemm<KC, KC, KC_GEMM_TN_MATVEC>(g, 1, c->stream)));
+            DN_HIP(c, ps.end());
+            return DN_OK;
+        }
+    }
+    for (int m = 1; m <= L; ++m) {
+        GemmProblem& p = g.p[m - 1];
+        p = mk_problem(left[m], c->ld[m], c->fptr(c->o_ZST[m - 1]), c->ld_s, c->fptr(c->o_tn) + pl.offset[m],
+                       c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
+        p.split_stride = tn_slice_floats(c, m);
+        p.c_rows_padded = 1;
+    }
+    ProfScope ps(c, KC_GEMM_TN_MATVEC);
+    DN_HIP(c, ps.err);
+    DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
+    DN_HIP(c, ps.end());
+    return DN_OK;
+}
+
 // out = G^S v (mode full / per-layer), Section 4.2 factored products on the stored blocks
 // dot, lambda: passed on to the fold of the sums over samples (not in partition mode)
 int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nullptr, float lambda = 0.f) {
@@ -415,24 +472,14 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
             DN_HIP(c, ps.end());
         }
     }
-    // 3. sums over samples for every layer: W_m = T^m^T [Z^{m-1}, 1] (the right operand transposed once by
-    //    dn_jacobian_prep: K-contiguous, the ones as a real row)
+    // 3. sums over samples for every layer
     TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
-        GemmGroup g;
-        g.nprob = L;
-        for (int m = 1; m <= L; ++m) {
-            GemmProblem& p = g.p[m - 1];
-            p = mk_problem(c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZST[m - 1]), c->ld_s,
-                           c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
-            p.split_stride = tn_slice_floats(c, m);
-            p.c_rows_padded = 1;
-        }
-        ProfScope ps(c, KC_GEMM_TN_MATVEC);
-        DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
-        DN_HIP(c, ps.end());
+        const float* left[DN_MAX_LAYERS + 1] = {nullptr};
+        for (int m = 1; m <= L; ++m) left[m] = c->fptr(c->o_T[m]);
+        const int rc = sums_over_samples(c, s, left, pl);
+        if (rc != DN_OK) return rc;
     }
     // 4. fold slices, scale by 1/|S|, add v/C
     return tn_reduce(c, &pl, false, v, out, 1.0 / (double)s, dot, lambda);

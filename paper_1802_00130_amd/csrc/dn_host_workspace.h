@@ -21,6 +21,7 @@ void layout_workspace(dn_ctx* c) {
     for (int m = 0; m <= L; ++m) c->o_ZS[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
     c->ld_s = round_up(c->s_max, 4);
     for (int m = 0; m < L; ++m) c->o_ZST[m] = take(cur, sizeof(float) * (size_t)(c->dims[m] + 1) * c->ld_s);
+    for (int m = 1; m <= L; ++m) c->o_TT[m] = take(cur, sizeof(float) * (size_t)c->dims[m] * c->ld_s);
     for (int m = 1; m < L; ++m) c->o_P[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->dims[L] * c->ld[m]);
     for (int m = 1; m <= L; ++m) c->o_Q[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);
     for (int m = 1; m <= L; ++m) c->o_T[m] = take(cur, sizeof(float) * (size_t)c->s_max * c->ld[m]);

@@ -114,6 +114,60 @@ __global__ __launch_bounds__(256) void transpose_ones_kernel(const float* __rest
     }
 }
 
+// dst_p[c][r] = src_p[r][c] for up to DN_MAX_LAYERS matrices of `rows` rows in one launch (64 x 64 tiles, 16-byte
+// accesses on both sides): the left operands T^m of the outer sums over samples (Section 4.2) with the sample index
+// contiguous, for the launches large enough that a K-contiguous operand pays for the copy.  Rows of dst are ld_dst
+// floats (a multiple of 4, >= rows rounded up to 4); the padding columns are written as zeros.
+struct TransposeArgs {
+    int nprob, rows, tiles_r;
+    const float* src[DN_MAX_LAYERS];
+    float* dst[DN_MAX_LAYERS];
+    long long ld_src[DN_MAX_LAYERS];
+    int cols[DN_MAX_LAYERS];
+    int first[DN_MAX_LAYERS + 1];     // first work-group of each matrix
+    long long ld_dst;
+};
+
+__global__ __launch_bounds__(256) void transpose_group_kernel(const TransposeArgs a) {
+    __shared__ float tile[64][65];
+    int p = 0;
+#pragma unroll
+    for (int i = 1; i < DN_MAX_LAYERS; ++i)
+        if (i < a.nprob && (int)blockIdx.x >= a.first[i]) p = i;
+    const int b = blockIdx.x - a.first[p];
+    const int r0 = (b % a.tiles_r) * 64, c0 = (b / a.tiles_r) * 64;
+    const int cols = a.cols[p];
+    const float* __restrict__ src = a.src[p];
+    float* __restrict__ dst = a.dst[p];
+    const long long lds = a.ld_src[p];
+    const int q = threadIdx.x & 15, w = threadIdx.x >> 4;      // 16 quads of columns x 16 rows per pass
+#pragma unroll
+    for (int k = 0; k < 64; k += 16) {
+        const int rr = r0 + w + k, cc = c0 + 4 * q;
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (rr < a.rows) {
+            const float* s4 = src + (long long)rr * lds + cc;
+            if (cc + 3 < cols) {
+                x = *reinterpret_cast<const float4*>(s4);
+            } else {
+                if (cc + 0 < cols) x.x = s4[0];
+                if (cc + 1 < cols) x.y = s4[1];
+                if (cc + 2 < cols) x.z = s4[2];
+            }
+        }
+        tile[w + k][4 * q + 0] = x.x; tile[w + k][4 * q + 1] = x.y;
+        tile[w + k][4 * q + 2] = x.z; tile[w + k][4 * q + 3] = x.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 64; k += 16) {
+        const int cc = c0 + w + k, rr = r0 + 4 * q;          // a row of dst, four consecutive samples
+        if (cc < cols && rr < a.rows)
+            *reinterpret_cast<float4*>(dst + (long long)cc * a.ld_dst + rr) =
+                make_float4(tile[4 * q + 0][w + k], tile[4 * q + 1][w + k], tile[4 * q + 2][w + k], tile[4 * q + 3][w + k]);
+    }
+}
+
 // Dense copy of a stored block (drops the row padding).
 __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                          long long rows, int cols, long long ld) {

@@ -662,19 +662,10 @@ int dn_gn_matvec_rop(dn_ctx* c, const float* v, float* out) {
     TnPlan pl = plan_tn_product(c, s);
     if (pl.total > c->tn_floats) return DN_ENOSPC;
     {
-        GemmGroup g;
-        g.nprob = L;
-        for (int m = 1; m <= L; ++m) {
-            GemmProblem& p = g.p[m - 1];
-            p = mk_problem(m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]), c->ld[m], c->fptr(c->o_ZST[m - 1]),
-                           c->ld_s, c->fptr(c->o_tn) + pl.offset[m], c->ldw[m], c->dims[m], c->dims[m - 1] + 1, s);
-            p.split_stride = tn_slice_floats(c, m);
-            p.c_rows_padded = 1;
-        }
-        ProfScope ps(c, KC_GEMM_TN_MATVEC);
-        DN_HIP(c, ps.err);
-        DN_HIP(c, (launch_gemm<RT, KC, KC_GEMM_TN_MATVEC>(g, pl.splits, c->stream)));
-        DN_HIP(c, ps.end());
+        const float* left[DN_MAX_LAYERS + 1] = {nullptr};
+        for (int m = 1; m <= L; ++m) left[m] = m == L ? c->fptr(c->o_Q[L]) : c->fptr(c->o_T[m]);
+        const int rc = sums_over_samples(c, s, left, pl);
+        if (rc != DN_OK) return rc;
     }
     return tn_reduce(c, &pl, false, v, out, 2.0 / (double)s);
 }

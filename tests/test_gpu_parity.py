@@ -335,6 +335,32 @@ def test_large_tiles_with_ragged_edges():
     w.ctx.close()
 
 
+def test_sums_over_samples_with_transposed_left_operand():
+    """A product whose sums over samples are large enough for the 128 x 128 tiles (512 of them: 4040 x 1858 and
+    10 x 4041, ragged in both dimensions): the left operands T^m are then transposed first and both operands read
+    K-contiguously.  Sums over 70 samples (four K-tiles and a ragged fifth), then over 37 of the 70 the context was
+    created for (the transposed buffers keep the row stride of the largest subsample)."""
+    cfg = dn_inputs.custom((1857, 4040, 10), l=100, s=70, C=20.0, seed=87)
+    w = Workload(cfg, bias_scale=0.3)
+    th64 = w.theta.astype(np.float64)
+    out = w.empty()
+    for S in (w.S, w.S[5:42]):
+        dn.dn_jacobian_prep(w.ctx, w.dtheta, w.dX, torch.from_numpy(np.ascontiguousarray(S)).to("cuda:0"))
+        XS = w.X[S].astype(np.float64)
+        v = dn_inputs.make_probe(cfg, 1)
+        for mode, fn in ((dn.DN_FULL, orc.gn_matvec), (dn.DN_BLOCKDIAG, orc.gn_matvec_blockdiag)):
+            ref = fn(th64, cfg.dims, cfg.C, XS, v.astype(np.float64))
+            out.fill_(float("nan"))
+            dn.dn_gn_matvec(w.ctx, w.dev(v), out, mode)
+            whole, worst = assert_close_blocks(out.cpu().numpy(), ref, cfg.dims, TOL, f"mode {mode}")
+            print(f"  {len(S)} samples, mode {mode}: rel err {whole:.2e}, worst block {worst}", flush=True)
+        out.fill_(float("nan"))
+        dn.dn_gn_matvec_rop(w.ctx, w.dev(v), out)
+        assert_close_blocks(out.cpu().numpy(), orc.gn_matvec(th64, cfg.dims, cfg.C, XS, v.astype(np.float64)), cfg.dims,
+                            TOL, "product without stored blocks")
+    w.ctx.close()
+
+
 def test_two_contexts_on_two_streams():
     """Two contexts for different networks, each bound to a stream of its own (default priority), with their
     calls interleaved from the host: every result matches the oracle, so nothing is shared between contexts
