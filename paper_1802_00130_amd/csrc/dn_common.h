@@ -18,6 +18,17 @@ __device__ __forceinline__ float dpp_move(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
 }
 
+// Four floats of a stored block, 16-byte aligned, fetched as a streaming (non-temporal) load: the blocks are read
+// once per product and are far larger than the caches, and a read that does not allocate there runs at 6.9-7.1 TB/s
+// on MI355X where a plain one reaches 6.1-6.3 (16 GB, float4 per lane, 2048 work-groups).  Used by the kernels that
+// stream blocks from HBM (teams of work-groups, two-pass kernels); the register-strip kernels serve narrow outputs,
+// whose blocks mostly fit the memory-side cache between products, and keep plain loads (measured: no gain there).
+typedef float dn_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream4(const float* p) {
+    const dn_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const dn_f32x4*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // Sum over the 64 lanes of a wave, result in lane 63 only, with DPP alone (no LDS traffic): rows of 16
 // lanes first, then row_bcast:15 adds the sum of row r-1 into rows 1 and 3, then row_bcast:31 adds the
 // sum of rows 0-1 into rows 2 and 3.

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void jv_jtv_band_kernel(const 
 #pragma unroll
             for (int k = 0; k < H; ++k) {
                 p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (live && k < nrow) p[k] = *reinterpret_cast<const float4*>(prow + (long long)k * ldm);
+                if (live && k < nrow) p[k] = load_stream4(prow + (long long)k * ldm);
             }
             // q^L of the band's rows (full mode) is fetched now, not after the wait
             float qL = 0.f;

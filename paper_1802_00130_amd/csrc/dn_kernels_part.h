@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void jv_part_kernel(const PartArgs a, const un
                 const int j = 4 * c4;
                 float4 p4[RW];
 #pragma unroll
-                for (int k = 0; k < RW; ++k) p4[k] = *reinterpret_cast<const float4*>(prow[k] + j);
+                for (int k = 0; k < RW; ++k) p4[k] = load_stream4(prow[k] + j);
                 if (j < lo || j + 3 >= hi) {
 #pragma unroll
                     for (int k = 0; k < RW; ++k) {
@@ -171,7 +171,7 @@ __device__ __forceinline__ void jtv_part_block(const PartArgs& a, int chunks_tot
     if (one_group) {
 #pragma unroll 4
         for (int u = 0; u < a.nL; ++u) {
-            const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
+            const float4 p4 = load_stream4(pcol + (long long)u * a.ld[m]);
 #pragma unroll
             for (int x = 0; x < DN_MAX_SPLIT; ++x)
                 if (x < ga) {
@@ -181,7 +181,7 @@ __device__ __forceinline__ void jtv_part_block(const PartArgs& a, int chunks_tot
         }
     } else {
         for (int u = 0; u < a.nL; ++u) {
-            const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
+            const float4 p4 = load_stream4(pcol + (long long)u * a.ld[m]);
             const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
             for (int x = 0; x < DN_MAX_SPLIT; ++x)

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void jv_rows_kernel(const StreamArgs a, const 
             double acc = 0.0;
 #pragma unroll 4
             for (int c = lane; c < nm4; c += 64) {
-                const float4 p4 = *reinterpret_cast<const float4*>(prow + 4 * c);
+                const float4 p4 = load_stream4(prow + 4 * c);
                 const float4 q4 = *reinterpret_cast<const float4*>(q + 4 * c);
                 acc += ((double)p4.x * q4.x + (double)p4.y * q4.y) + ((double)p4.z * q4.z + (double)p4.w * q4.w);
             }
@@ -114,7 +114,7 @@ __device__ __forceinline__ void jtv_cols_block(const StreamArgs& a, int chunks_t
     // rows are padded to a multiple of 4 floats, so a full float4 is always readable
 #pragma unroll 8
     for (int u = 0; u < a.nL; ++u) {
-        const float4 p4 = *reinterpret_cast<const float4*>(pcol + (long long)u * a.ld[m]);
+        const float4 p4 = load_stream4(pcol + (long long)u * a.ld[m]);
         const double w = (double)rbar[u];
         ax += p4.x * w; ay += p4.y * w; az += p4.z * w; aw += p4.w * w;
     }
