@@ -347,7 +347,7 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
         // Small launches (a few tiles per CU) whose longest sum over t is at least twice any other: cut that
         // layer's sum in two halves, written to Q^m and a second buffer that the fused kernel adds on the way
         // in.  The launch then consists of tiles of similar length (measured at 784-300-300-10, |S| = 3000:
-        // 30.2 -> 26.8 us).
+        // 30.2 -> 26.8 us; at 3072-1000-500-10, 1000 tiles, it gains nothing: 173 -> 176 us).
         if (fused && L < DN_MAX_GROUP && group_tiles(g, 64, 64) <= 3 * c->num_cus) {
             int big = 0;                       // among the hidden layers: Q^L is read as it is
             for (int k = 1; k + 1 < L; ++k)
@@ -357,7 +357,10 @@ int gn_matvec(dn_ctx* c, const float* v, float* out, int mode, double* dot = nul
                 if (k != big) other = std::max(other, g.p[k].K);
             if (g.p[big].K >= 512 && g.p[big].K >= 2 * other) {
                 const int kh = (int)round_up(g.p[big].K / 2, 16);
-                GemmProblem& second = g.p[g.nprob++];
+                // the second half right behind the first, so that the walk still has its longest tiles first
+                for (int k = g.nprob; k > big + 1; --k) g.p[k] = g.p[k - 1];
+                ++g.nprob;
+                GemmProblem& second = g.p[big + 1];
                 second = g.p[big];
                 second.A += kh;
                 second.B += kh;
