@@ -695,6 +695,11 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 1)) void gemm_kern
             } else {
                 const float* __restrict__ prep = P.pre ? P.pre + (long long)mb * P.ldpre + n : nullptr;
                 const float* __restrict__ addp = P.add ? P.add + (long long)mb * P.ldadd + n : nullptr;
+                // activation row of output row mb + dm: one division per block of 32 rows instead of one per element
+                // (the 28 rows a lane holds cross a multiple of auxdiv at most once when auxdiv >= 28)
+                const int aux_q = P.aux ? mb / P.auxdiv : 0;
+                const int aux_r = P.aux ? mb - aux_q * P.auxdiv : 0;
+                const bool aux_fast = P.auxdiv >= 28;                                          // uniform
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int dm = 8 * (e / 4) + (e % 4);
@@ -703,7 +708,10 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 1)) void gemm_kern
                     if (prep) x += prep[(long long)dm * P.ldpre];
                     if (P.sigmoid) x = sigmoidf_fast(x);
                     if (P.aux) {
-                        const float z = P.aux[(long long)((mb + dm) / P.auxdiv) * P.ldaux + n];
+                        const int arow = P.auxdiv == 1 ? mb + dm
+                                         : aux_fast    ? aux_q + (aux_r + dm >= P.auxdiv ? 1 : 0)
+                                                       : (mb + dm) / P.auxdiv;
+                        const float z = P.aux[(long long)arow * P.ldaux + n];
                         x *= z * (1.0f - z);
                     }
                     if (addp) x += addp[(long long)dm * P.ldadd];
