@@ -137,6 +137,9 @@ __device__ __forceinline__ void cg_sweep(long long lo, long long hi, FV fv, FS f
 }
 __device__ __forceinline__ f32x4v ld4(const float* p) { return *reinterpret_cast<const f32x4v*>(p); }
 __device__ __forceinline__ void st4(float* p, f32x4v v) { *reinterpret_cast<f32x4v*>(p) = v; }
+// streaming variants for vectors that nothing reads again soon (no allocation in the caches)
+__device__ __forceinline__ f32x4v ld4_stream(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(p)); }
+__device__ __forceinline__ void st4_stream(float* p, f32x4v v) { __builtin_nontemporal_store(v, reinterpret_cast<f32x4v*>(p)); }
 
 // d = 0, r = p = -g, partial g^T g
 __global__ __launch_bounds__(256) void cg_init_kernel(const CgSegs sg, const float* __restrict__ g,
@@ -226,8 +229,8 @@ __global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, cons
     double acc = 0.0;
     cg_sweep(lo, hi,
              [&](long long e) {
-                 const f32x4v pe = ld4(p + e), qe = ld4(q + e);
-                 f32x4v de = ld4(d + e), re = ld4(r + e);
+                 const f32x4v pe = ld4(p + e), qe = ld4_stream(q + e);
+                 f32x4v de = ld4_stream(d + e), re = ld4(r + e);
                  double s4[4];
 #pragma unroll
                  for (int k = 0; k < 4; ++k) {
@@ -235,7 +238,7 @@ __global__ __launch_bounds__(256) void cg_update_dr_kernel(const CgSegs sg, cons
                      re[k] = re[k] - alpha * (qe[k] + lambda * pe[k]);
                      s4[k] = (double)re[k] * (double)re[k];
                  }
-                 st4(d + e, de); st4(r + e, re);
+                 st4_stream(d + e, de); st4(r + e, re);
                  acc += (s4[0] + s4[1]) + (s4[2] + s4[3]);
              },
              [&](long long e) {
