@@ -82,6 +82,17 @@ size_t dn_workspace_bytes(const dn_ctx* ctx);
 int dn_product_slices(const dn_ctx* ctx, int s);
 
 /*
+ * Host-only: which of nprob (1..8) dense products C_i[M_i x N_i] = A_i[M_i x K_i] B_i[N_i x K_i]^T, issued as ONE
+ * launch of the tile engine with both operands K-contiguous (the forward pass of Section 2.1, the back-propagation of
+ * Section 2.2, the sweeps of Section 3.3, the inner sums of Section 4.2), go through 128 x 128 tiles (large[i] = 1)
+ * and which through 64 x 64 tiles (large[i] = 0).  Large tiles are taken when there are at least 512 of them, they
+ * fill whole rounds of work-groups and lose little to padding; a launch may be split into a large-tile and a
+ * small-tile part.  Returns the number of problems on large tiles, or DN_EINVAL (null pointers, nprob outside 1..8,
+ * a non-positive size).  No device is touched; for tests of the launch planning.
+ */
+int dn_gemm_large_tiles(int nprob, const int* M, const int* N, const int* K, int* large);
+
+/*
  * Lend the context a device workspace of at least dn_workspace_bytes() bytes, 256-byte
  * aligned, and the HIP stream (hipStream_t passed as void*, NULL = default stream) on which
  * all later work is enqueued.  Invalidates a previous dn_jacobian_prep.

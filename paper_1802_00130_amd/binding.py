@@ -70,6 +70,7 @@ def load_library() -> ctypes.CDLL:
         "dn_num_params": (sz, [vp]),
         "dn_workspace_bytes": (sz, [vp]),
         "dn_product_slices": (i, [vp, i]),
+        "dn_gemm_large_tiles": (i, [i, P(i), P(i), P(i), P(i)]),
         "dn_bind": (i, [vp, vp, sz, vp]),
         "dn_forward": (i, [vp, vp, vp, vp, i, P(d), vp]),
         "dn_forward_static": (i, [i, P(i), d, vp, vp, vp, i, vp, P(d), vp]),
@@ -105,7 +106,8 @@ def load_library() -> ctypes.CDLL:
 
 
 EXPORTED_SYMBOLS = (
-    "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_product_slices", "dn_bind", "dn_forward",
+    "dn_strerror", "dn_create", "dn_destroy", "dn_num_params", "dn_workspace_bytes", "dn_product_slices", "dn_gemm_large_tiles", "dn_bind",
+    "dn_forward",
     "dn_forward_static", "dn_grad", "dn_jacobian_prep", "dn_jacobian_read", "dn_gn_matvec", "dn_gn_matvec_rop", "dn_cg", "dn_cg_sync",
     "dn_set_split", "dn_num_partitions", "dn_newton_step", "dn_set_stream_passes", "dn_set_spin_limit",
     "dn_sync_status", "dn_profile_enable", "dn_profile_select", "dn_profile_reset", "dn_profile_num_classes",

@@ -118,6 +118,23 @@ int dn_product_slices(const dn_ctx* c, int s) {
     return pl.total <= c->tn_floats ? pl.splits : DN_ENOSPC;
 }
 
+int dn_gemm_large_tiles(int nprob, const int* M, const int* N, const int* K, int* large) {
+    if (!M || !N || !K || !large || nprob < 1 || nprob > DN_MAX_GROUP) return DN_EINVAL;
+    GemmGroup g;
+    g.nprob = nprob;
+    for (int i = 0; i < nprob; ++i) {
+        if (M[i] < 1 || N[i] < 1 || K[i] < 1) return DN_EINVAL;
+        g.p[i] = mk_problem(nullptr, K[i], nullptr, K[i], nullptr, N[i], M[i], N[i], K[i]);
+    }
+    const unsigned mask = pick_128(g);
+    int count = 0;
+    for (int i = 0; i < nprob; ++i) {
+        large[i] = (mask >> i) & 1u;
+        count += large[i];
+    }
+    return count;
+}
+
 int dn_bind(dn_ctx* c, void* d_workspace, size_t bytes, void* hip_stream) {
     if (!c || !d_workspace) return DN_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0) return DN_EINVAL;

@@ -170,3 +170,35 @@ def test_product_plan_fits_the_workspace_for_every_subsample_size(lib):
         assert len(set(counts)) >= 2
         lib.dn_destroy(h)
     assert lib.dn_product_slices(None, 1) == -1
+
+
+def test_large_tiles_are_chosen_for_whole_rounds_only(lib):
+    """Host logic of the tile engine: 128 x 128 tiles need at least 512 tiles that fill whole rounds of 256 and lose
+    little to padding; a grouped launch may send its large problems through them and the rest through small tiles."""
+    import ctypes
+
+    def plan(*problems):
+        n = len(problems)
+        arr = lambda k: (ctypes.c_int * n)(*[p[k] for p in problems])
+        large = (ctypes.c_int * n)()
+        rc = lib.dn_gemm_large_tiles(n, arr(0), arr(1), arr(2), large)
+        return rc, list(large)
+
+    assert plan((200000, 4096, 4096)) == (1, [1])                  # forward pass of the largest configuration
+    assert plan((2000000, 4096, 4096)) == (1, [1])                 # its sweeps over the stored blocks
+    assert plan((100000, 2000, 2048)) == (1, [1])
+    assert plan((2000, 4096, 4096)) == (1, [1])                    # 512 tiles: two rounds exactly
+    assert plan((5000, 2000, 2048)) == (0, [0])                    # 640 tiles: two and a half rounds
+    assert plan((3000, 300, 784)) == (0, [0])                      # too few tiles
+    assert plan((60000, 300, 784)) == (0, [0])                     # 300 columns: 384 with large tiles, 320 with small
+    # inner sums of the largest configuration: four layers of 512 large tiles, the narrow last layer on small tiles
+    assert plan(*([(2000, 4096, 4096)] * 4 + [(2000, 1000, 4096)])) == (4, [1, 1, 1, 1, 0])
+    # a group that passes as a whole stays whole
+    assert plan((4096, 4097, 2000), (4096, 4097, 2000), (4096, 4097, 2000), (4096, 4097, 2000), (1000, 4097, 2000))[0] == 5
+    # argument checks
+    one = (ctypes.c_int * 1)(64)
+    assert lib.dn_gemm_large_tiles(0, one, one, one, one) == -1
+    assert lib.dn_gemm_large_tiles(9, one, one, one, one) == -1
+    assert lib.dn_gemm_large_tiles(1, None, one, one, one) == -1
+    zero = (ctypes.c_int * 1)(0)
+    assert lib.dn_gemm_large_tiles(1, zero, one, one, one) == -1
