@@ -101,8 +101,8 @@ bool prefer_128(const GemmGroup& g, unsigned only = ~0u) {
 // Which problems of a group go through the large tiles: all of them if the whole group passes the test above;
 // else the problems with at least a round of large tiles each, if they pass it among themselves (the rest then
 // gets a launch of small tiles of its own: the inner sums of 4096 x 5 - 1000 over 2000 samples are four layers of 512
-// large tiles, exactly four rounds, and a fifth of 128, which as small tiles costs 0.13 ms instead of a fifth round:
-// 2.43 -> 2.1 ms); else none.
+// large tiles, exactly four rounds, and a fifth of 128, which as small tiles costs 0.15 ms instead of a fifth round:
+// 2.43 -> 2.32 ms); else none.
 unsigned pick_128(const GemmGroup& g) {
     const unsigned all = g.nprob >= 32 ? ~0u : ((1u << g.nprob) - 1u);
     if (prefer_128(g, all)) return all;
